@@ -1,0 +1,586 @@
+// C-ABI entry points and the Newton-Schulz workspace plan.
+//
+// Working layout.  Weight blocks of equal shape form a class; a class keeps its
+// matrices back to back as [block][worker][rows_p][cols_p] bf16 with both
+// dimensions zero-padded to multiples of 64 (padding rows/columns stay zero
+// through the iteration, so they change nothing).  One grouped GEMM launch then
+// covers every class, block and worker of a Newton-Schulz half-step.
+#include <math.h>
+
+#include <algorithm>
+
+#include "common.h"
+
+struct ns_class {
+  int rows = 0, cols = 0;  // logical shape
+  int rp = 0, cp = 0;      // padded shape
+  bool wide = true;        // rows <= cols: Gram over the rows (Y Y^T), else over the columns (Y^T Y)
+  int s = 0, l = 0;        // padded short / long side
+  int count = 0;           // blocks of this shape
+  std::vector<int> members;
+  long long mat = 0;       // rp * cp
+  // arena offsets in bytes
+  size_t off_x[2] = {0, 0}, off_xt = 0, off_b = 0, off_a = 0, off_sig = 0, off_inv = 0, off_partial = 0;
+  int chunks = 0;          // momentum chunks per worker
+};
+
+struct ns_plan {
+  std::vector<int> rows, cols;
+  int M = 0;
+  bool quintic = false;
+  int sign_fmt = -1;
+  std::vector<ns_class> classes;
+  std::vector<int> class_of, index_in_class;  // per block
+  std::vector<size_t> off_signs;              // per block, internal sign buffers (M rows)
+  std::vector<long long> sign_stride;         // per block, bytes per worker
+  size_t off_pi = 0;                          // power-iteration scratch
+  size_t total = 0;
+};
+
+void sm_plan_free(signmuon_ctx* ctx) {
+  delete ctx->plan;
+  ctx->plan = nullptr;
+}
+
+int sm_launch_fill(signmuon_ctx* ctx, float* p, int n, float v);  // stream.hip
+
+namespace {
+
+template <typename T>
+T* at(signmuon_ctx* ctx, size_t off) {
+  return reinterpret_cast<T*>(reinterpret_cast<unsigned char*>(ctx->arena) + off);
+}
+
+int get_plan(signmuon_ctx* ctx, int n, const int* rows, const int* cols, int M, bool quintic, int sign_fmt,
+             ns_plan** out) {
+  ns_plan* pl = ctx->plan;
+  if (pl && pl->M == M && pl->quintic == quintic && pl->sign_fmt == sign_fmt && (int)pl->rows.size() == n &&
+      std::equal(rows, rows + n, pl->rows.begin()) && std::equal(cols, cols + n, pl->cols.begin())) {
+    *out = pl;
+    return SM_OK;
+  }
+  sm_plan_free(ctx);
+  pl = new ns_plan();
+  pl->rows.assign(rows, rows + n);
+  pl->cols.assign(cols, cols + n);
+  pl->M = M;
+  pl->quintic = quintic;
+  pl->sign_fmt = sign_fmt;
+  pl->class_of.resize(n);
+  pl->index_in_class.resize(n);
+  for (int i = 0; i < n; ++i) {
+    int k = -1;
+    for (size_t j = 0; j < pl->classes.size(); ++j)
+      if (pl->classes[j].rows == rows[i] && pl->classes[j].cols == cols[i]) k = (int)j;
+    if (k < 0) {
+      ns_class c;
+      c.rows = rows[i];
+      c.cols = cols[i];
+      c.rp = (int)sm_round_up(rows[i], 64);
+      c.cp = (int)sm_round_up(cols[i], 64);
+      c.wide = rows[i] <= cols[i];
+      c.s = c.wide ? c.rp : c.cp;
+      c.l = c.wide ? c.cp : c.rp;
+      c.mat = (long long)c.rp * c.cp;
+      c.chunks = (int)(((long long)rows[i] * cols[i] + SM_MOM_CHUNK - 1) / SM_MOM_CHUNK);
+      pl->classes.push_back(c);
+      k = (int)pl->classes.size() - 1;
+    }
+    pl->class_of[i] = k;
+    pl->index_in_class[i] = pl->classes[k].count++;
+    pl->classes[k].members.push_back(i);
+  }
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t o = off;
+    off += (bytes + 255) / 256 * 256;
+    return o;
+  };
+  long long max_pi = 0;
+  for (auto& c : pl->classes) {
+    const long long batch = (long long)c.count * M;
+    c.off_x[0] = take((size_t)batch * c.mat * 2);
+    c.off_x[1] = take((size_t)batch * c.mat * 2);
+    c.off_xt = take((size_t)batch * c.mat * 2);
+    c.off_b = take((size_t)batch * c.s * c.s * 2);
+    c.off_a = quintic ? take((size_t)batch * c.s * c.s * 2) : 0;
+    c.off_sig = take((size_t)batch * 4);
+    c.off_inv = take((size_t)batch * 4);
+    c.off_partial = take((size_t)batch * c.chunks * 4);
+    max_pi = std::max(max_pi, (long long)M * (c.rows + c.cols));
+  }
+  pl->off_pi = take((size_t)max_pi * 4);
+  pl->off_signs.resize(n);
+  pl->sign_stride.resize(n);
+  for (int i = 0; i < n; ++i) {
+    const long long d = (long long)rows[i] * cols[i];
+    pl->sign_stride[i] = (sign_fmt == SM_SIGN_INT8) ? sm_round_up(d, 16) : 8 * ((d + 63) / 64);
+    pl->off_signs[i] = (sign_fmt < 0) ? 0 : take((size_t)pl->sign_stride[i] * M);
+  }
+  pl->total = off;
+  int rc = sm_arena_reserve(ctx, pl->total);
+  if (rc != SM_OK) {
+    delete pl;
+    return rc;
+  }
+  // padding must read as zero
+  SM_HIP(ctx, hipMemsetAsync(ctx->arena, 0, pl->total, ctx->stream));
+  ctx->plan = pl;
+  *out = pl;
+  return SM_OK;
+}
+
+// Runs `steps` Newton-Schulz steps on every class, batch = count * mult per class,
+// starting from buffer `cur` (0/1) of each class.  Scales the first step by the
+// per-item inv_sigma when use_scale.  Returns the buffer index holding the result.
+int run_ns(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coeffs, bool use_scale, int* cur_io) {
+  int cur = *cur_io;
+  const float a = coeffs[0], b = coeffs[1], c = coeffs[2];
+  const int ncls = (int)pl->classes.size();
+  for (int k = 0; k < steps; ++k) {
+    const bool sc = use_scale && k == 0;
+    // transposed copies: tall classes need Y^T (K-contiguous rows) for the Gram
+    for (auto& cl : pl->classes) {
+      if (cl.wide) continue;
+      int rc = sm_launch_transpose(ctx, at<bf16_t>(ctx, cl.off_x[cur]), cl.rp, cl.cp, cl.cp, cl.mat,
+                                   at<bf16_t>(ctx, cl.off_xt), cl.rp, cl.mat, cl.count * mult);
+      if (rc != SM_OK) return rc;
+    }
+    // Gram: Bm = a I + b s^2 G (+ c (s^2 G)^2), G = Y Y^T over the short side
+    for (int c0 = 0; c0 < ncls; c0 += SM_GEMM_MAX_PROB) {
+      const int g = std::min(ncls - c0, SM_GEMM_MAX_PROB);
+      sm_gemm_args ga;
+      ga.n_prob = g;
+      ga.scale_pow = sc ? 2 : 0;
+      ga.alpha = (c != 0.f) ? 1.f : b;
+      ga.gamma = 0.f;
+      ga.diag = (c != 0.f) ? 0.f : a;
+      ga.pad_ = 0;
+      for (int i = 0; i < g; ++i) {
+        ns_class& cl = pl->classes[c0 + i];
+        sm_gemm_prob& P = ga.p[i];
+        const bf16_t* y = cl.wide ? at<bf16_t>(ctx, cl.off_x[cur]) : at<bf16_t>(ctx, cl.off_xt);
+        P.A = y;
+        P.B = y;
+        P.C = (c != 0.f) ? at<bf16_t>(ctx, cl.off_a) : at<bf16_t>(ctx, cl.off_b);
+        P.R = nullptr;
+        P.scale = sc ? at<float>(ctx, cl.off_inv) : nullptr;
+        P.sA = P.sB = cl.mat;
+        P.sC = (long long)cl.s * cl.s;
+        P.M = P.N = cl.s;
+        P.K = cl.l;
+        P.lda = P.ldb = cl.l;
+        P.ldc = cl.s;
+        P.batch = cl.count * mult;
+        P.pad_ = 0;
+      }
+      int rc = sm_launch_gemm_nt(ctx, ga, SM_K_NS_GRAM);
+      if (rc != SM_OK) return rc;
+      if (c != 0.f) {  // Bm = c A A^T + b A + a I   (A symmetric)
+        ga.scale_pow = 0;
+        ga.alpha = c;
+        ga.gamma = b;
+        ga.diag = a;
+        for (int i = 0; i < g; ++i) {
+          ns_class& cl = pl->classes[c0 + i];
+          sm_gemm_prob& P = ga.p[i];
+          P.A = P.B = P.R = at<bf16_t>(ctx, cl.off_a);
+          P.C = at<bf16_t>(ctx, cl.off_b);
+          P.scale = nullptr;
+          P.sA = P.sB = P.sC = (long long)cl.s * cl.s;
+          P.M = P.N = P.K = cl.s;
+          P.lda = P.ldb = P.ldc = cl.s;
+        }
+        rc = sm_launch_gemm_nt(ctx, ga, SM_K_NS_GRAM);
+        if (rc != SM_OK) return rc;
+      }
+    }
+    // wide classes need Y^T as the K-contiguous second operand of Bm * Y
+    for (auto& cl : pl->classes) {
+      if (!cl.wide) continue;
+      int rc = sm_launch_transpose(ctx, at<bf16_t>(ctx, cl.off_x[cur]), cl.rp, cl.cp, cl.cp, cl.mat,
+                                   at<bf16_t>(ctx, cl.off_xt), cl.rp, cl.mat, cl.count * mult);
+      if (rc != SM_OK) return rc;
+    }
+    // apply: Y' = s * Bm Y (wide) or s * Y Bm (tall)
+    for (int c0 = 0; c0 < ncls; c0 += SM_GEMM_MAX_PROB) {
+      const int g = std::min(ncls - c0, SM_GEMM_MAX_PROB);
+      sm_gemm_args ga;
+      ga.n_prob = g;
+      ga.scale_pow = sc ? 1 : 0;
+      ga.alpha = 1.f;
+      ga.gamma = 0.f;
+      ga.diag = 0.f;
+      ga.pad_ = 0;
+      for (int i = 0; i < g; ++i) {
+        ns_class& cl = pl->classes[c0 + i];
+        sm_gemm_prob& P = ga.p[i];
+        if (cl.wide) {  // C[rp][cp] = Bm[rp][rp] * (Yt[cp][rp])^T
+          P.A = at<bf16_t>(ctx, cl.off_b);
+          P.B = at<bf16_t>(ctx, cl.off_xt);
+          P.sA = (long long)cl.s * cl.s;
+          P.sB = cl.mat;
+          P.lda = cl.s;
+          P.ldb = cl.rp;
+          P.K = cl.rp;
+        } else {        // C[rp][cp] = Y[rp][cp] * (Bm[cp][cp])^T, Bm symmetric
+          P.A = at<bf16_t>(ctx, cl.off_x[cur]);
+          P.B = at<bf16_t>(ctx, cl.off_b);
+          P.sA = cl.mat;
+          P.sB = (long long)cl.s * cl.s;
+          P.lda = cl.cp;
+          P.ldb = cl.s;
+          P.K = cl.cp;
+        }
+        P.C = at<bf16_t>(ctx, cl.off_x[cur ^ 1]);
+        P.R = nullptr;
+        P.scale = sc ? at<float>(ctx, cl.off_inv) : nullptr;
+        P.sC = cl.mat;
+        P.M = cl.rp;
+        P.N = cl.cp;
+        P.ldc = cl.cp;
+        P.batch = cl.count * mult;
+        P.pad_ = 0;
+      }
+      int rc = sm_launch_gemm_nt(ctx, ga, SM_K_NS_APPLY);
+      if (rc != SM_OK) return rc;
+    }
+    cur ^= 1;
+  }
+  *cur_io = cur;
+  return SM_OK;
+}
+
+bool bad_coeffs(const float* c) { return !c || !isfinite(c[0]) || !isfinite(c[1]) || !isfinite(c[2]); }
+
+}  // namespace
+
+extern "C" {
+
+int signmuon_momentum(signmuon_ctx* ctx, float* mom, const float* grad, const float* w, int M, int rows, int cols,
+                      float beta, float weight_decay, void* x_bf16, float* sumsq) {
+  if (!ctx) return SM_EINVAL;
+  if (!mom || !grad || M < 1 || rows < 1 || cols < 1) return sm_fail(ctx, SM_EINVAL, "momentum: bad pointer or size");
+  if (weight_decay != 0.f && !w) return sm_fail(ctx, SM_EINVAL, "momentum: weight_decay != 0 needs w");
+  if (!(beta >= 0.f && beta < 1.f)) return sm_fail(ctx, SM_EINVAL, "momentum: beta must be in [0, 1)");
+  if (!sm_aligned(mom, 4) || !sm_aligned(grad, 4) || (x_bf16 && !sm_aligned(x_bf16, 2)))
+    return sm_fail(ctx, SM_EINVAL, "momentum: misaligned pointer");
+  const long long d = (long long)rows * cols;
+  const int chunks = (int)((d + SM_MOM_CHUNK - 1) / SM_MOM_CHUNK);
+  float* partial = nullptr;
+  if (sumsq) {
+    // the partial sums go to the start of the arena, which may hold a plan's matrices: drop the plan
+    sm_plan_free(ctx);
+    int rc = sm_arena_reserve(ctx, (size_t)M * chunks * 4);
+    if (rc != SM_OK) return rc;
+    partial = reinterpret_cast<float*>(ctx->arena);
+  }
+  sm_mom_desc D;
+  D.mom = mom;
+  D.grad = grad;
+  D.w = (weight_decay != 0.f) ? w : nullptr;
+  D.x = reinterpret_cast<bf16_t*>(x_bf16);
+  D.partial = partial;
+  D.d = d;
+  D.x_stride = d;
+  D.cols = cols;
+  D.ld = cols;
+  D.chunks = chunks;
+  D.block_begin = 0;
+  int rc = sm_launch_momentum(ctx, &D, 1, M, beta, weight_decay);
+  if (rc != SM_OK) return rc;
+  if (sumsq) return sm_launch_reduce_partials(ctx, partial, chunks, M, sumsq);
+  return SM_OK;
+}
+
+int signmuon_polar_ns(signmuon_ctx* ctx, void* x, int dtype, int batch, int rows, int cols, const float* coeffs,
+                      int steps, int scale, int power_iters, float eps, const float* v0) {
+  if (!ctx) return SM_EINVAL;
+  if (!x || batch < 1 || rows < 1 || cols < 1 || steps < 0) return sm_fail(ctx, SM_EINVAL, "polar_ns: bad pointer or size");
+  if (dtype != SM_F32 && dtype != SM_BF16) return sm_fail(ctx, SM_EINVAL, "polar_ns: bad dtype");
+  if (bad_coeffs(coeffs)) return sm_fail(ctx, SM_EINVAL, "polar_ns: bad coeffs");
+  if (scale != SM_SCALE_FRO && scale != SM_SCALE_SPECTRAL && scale != SM_SCALE_NONE)
+    return sm_fail(ctx, SM_EINVAL, "polar_ns: bad scale");
+  if (scale == SM_SCALE_SPECTRAL && (!v0 || power_iters < 0))
+    return sm_fail(ctx, SM_EINVAL, "polar_ns: spectral scale needs v0 and power_iters >= 0");
+  if (!(eps >= 0.f)) return sm_fail(ctx, SM_EINVAL, "polar_ns: eps must be >= 0");
+  if (!sm_aligned(x, dtype == SM_F32 ? 4 : 2)) return sm_fail(ctx, SM_EINVAL, "polar_ns: misaligned x");
+  ns_plan* pl = nullptr;
+  int rc = get_plan(ctx, 1, &rows, &cols, batch, coeffs[2] != 0.f, -1, &pl);
+  if (rc != SM_OK) return rc;
+  ns_class& cl = pl->classes[0];
+  rc = sm_launch_copy_in(ctx, x, dtype, batch, rows, cols, at<bf16_t>(ctx, cl.off_x[0]), cl.cp, cl.mat);
+  if (rc != SM_OK) return rc;
+  bool use_scale = false;
+  if (scale == SM_SCALE_FRO) {
+    rc = sm_launch_sumsq(ctx, x, dtype, (long long)rows * cols, batch, at<float>(ctx, cl.off_partial),
+                         at<float>(ctx, cl.off_sig));
+    if (rc != SM_OK) return rc;
+    rc = sm_launch_inv_sigma(ctx, at<float>(ctx, cl.off_sig), batch, eps, true, at<float>(ctx, cl.off_inv));
+    if (rc != SM_OK) return rc;
+    use_scale = true;
+  } else if (scale == SM_SCALE_SPECTRAL) {
+    rc = sm_launch_power_iter(ctx, at<bf16_t>(ctx, cl.off_x[0]), rows, cols, cl.cp, cl.mat, batch, power_iters, eps, v0,
+                              cols, at<float>(ctx, pl->off_pi), at<float>(ctx, cl.off_sig));
+    if (rc != SM_OK) return rc;
+    rc = sm_launch_inv_sigma(ctx, at<float>(ctx, cl.off_sig), batch, eps, false, at<float>(ctx, cl.off_inv));
+    if (rc != SM_OK) return rc;
+    use_scale = true;
+  }
+  int cur = 0;
+  rc = run_ns(ctx, pl, batch, steps, coeffs, use_scale, &cur);
+  if (rc != SM_OK) return rc;
+  return sm_launch_copy_out(ctx, at<bf16_t>(ctx, cl.off_x[cur]), cl.cp, cl.mat, batch, rows, cols, x, dtype,
+                            (steps == 0 && use_scale) ? at<float>(ctx, cl.off_inv) : nullptr);
+}
+
+int signmuon_sign_pack(signmuon_ctx* ctx, const void* u, int dtype, int batch, int64_t n, int fmt, void* out,
+                       int64_t out_stride_bytes) {
+  if (!ctx) return SM_EINVAL;
+  if (!out || batch < 0 || n < 0 || (!u && n > 0 && batch > 0)) return sm_fail(ctx, SM_EINVAL, "sign_pack: bad pointer or size");
+  if (dtype != SM_F32 && dtype != SM_BF16) return sm_fail(ctx, SM_EINVAL, "sign_pack: bad dtype");
+  if (fmt != SM_SIGN_1BIT && fmt != SM_SIGN_INT8) return sm_fail(ctx, SM_EINVAL, "sign_pack: bad fmt");
+  if (n > 0x7FFFFFFFLL * 8) return sm_fail(ctx, SM_EINVAL, "sign_pack: n too large");
+  if (fmt == SM_SIGN_1BIT) {
+    if (out_stride_bytes % 8 || out_stride_bytes < 8 * ((n + 63) / 64) || !sm_aligned(out, 8))
+      return sm_fail(ctx, SM_EINVAL, "sign_pack: 1-bit rows must be 8-byte aligned and hold ceil(n/64) words");
+  } else if (out_stride_bytes < n) {
+    return sm_fail(ctx, SM_EINVAL, "sign_pack: int8 stride shorter than n");
+  }
+  if (!sm_aligned(u, dtype == SM_F32 ? 4 : 2)) return sm_fail(ctx, SM_EINVAL, "sign_pack: misaligned u");
+  if (batch == 0 || n == 0) return SM_OK;
+  if (batch > 65535) return sm_fail(ctx, SM_EUNSUPPORTED, "sign_pack: batch > 65535");
+  // treat each row as a 1 x n matrix; int counts are fine because cols is only used when ld != cols
+  if (n > 0x7FFFFFFF) {
+    // split long rows into 2-D with cols a multiple of 64 when possible
+    return sm_fail(ctx, SM_EUNSUPPORTED, "sign_pack: n >= 2^31 per row");
+  }
+  return sm_launch_sign_pack(ctx, u, dtype, batch, 1, (int)n, (int)n, n, fmt, out, out_stride_bytes);
+}
+
+int signmuon_majority_vote(signmuon_ctx* ctx, const void* signs, int fmt, int M, int64_t n, int64_t stride_bytes,
+                           void* voted, int vfmt, int32_t* counts, float* w, float lr_scaled) {
+  if (!ctx) return SM_EINVAL;
+  if (M < 1 || n < 0 || (!signs && n > 0)) return sm_fail(ctx, SM_EINVAL, "majority_vote: bad pointer or size");
+  if (fmt != SM_SIGN_1BIT && fmt != SM_SIGN_INT8) return sm_fail(ctx, SM_EINVAL, "majority_vote: bad fmt");
+  if (voted && (vfmt < SM_VOTE_BITS || vfmt > SM_VOTE_F32)) return sm_fail(ctx, SM_EINVAL, "majority_vote: bad vfmt");
+  if (n >= (1LL << 40)) return sm_fail(ctx, SM_EINVAL, "majority_vote: n too large");
+  if (fmt == SM_SIGN_1BIT) {
+    if (stride_bytes % 8 || stride_bytes < 8 * ((n + 63) / 64) || !sm_aligned(signs, 8))
+      return sm_fail(ctx, SM_EINVAL, "majority_vote: 1-bit rows must be 8-byte aligned and hold ceil(n/64) words");
+  } else if (stride_bytes < n) {
+    return sm_fail(ctx, SM_EINVAL, "majority_vote: int8 stride shorter than n");
+  }
+  if (voted && vfmt == SM_VOTE_BITS && !sm_aligned(voted, 8)) return sm_fail(ctx, SM_EINVAL, "majority_vote: misaligned voted bits");
+  if (voted && vfmt == SM_VOTE_BF16 && !sm_aligned(voted, 8)) return sm_fail(ctx, SM_EINVAL, "majority_vote: voted bf16 needs 8-byte alignment");
+  if (voted && vfmt == SM_VOTE_F32 && !sm_aligned(voted, 16)) return sm_fail(ctx, SM_EINVAL, "majority_vote: voted f32 needs 16-byte alignment");
+  if (voted && vfmt == SM_VOTE_INT8 && !sm_aligned(voted, 4)) return sm_fail(ctx, SM_EINVAL, "majority_vote: voted int8 needs 4-byte alignment");
+  if ((counts && !sm_aligned(counts, 16)) || (w && !sm_aligned(w, 16)))
+    return sm_fail(ctx, SM_EINVAL, "majority_vote: counts and w need 16-byte alignment");
+  if (n == 0) return SM_OK;
+  sm_vote_args a;
+  a.signs = signs;
+  a.fmt = fmt;
+  a.M = M;
+  a.n = n;
+  a.stride_bytes = stride_bytes;
+  a.voted = voted;
+  a.vfmt = vfmt;
+  a.cols = 1;
+  a.ld = 1;
+  a.counts = counts;
+  a.w = w;
+  a.lr_scaled = lr_scaled;
+  return sm_launch_vote(ctx, a);
+}
+
+int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
+  if (!ctx) return SM_EINVAL;
+  if (!s || s->n_mats < 1 || s->M < 1 || !s->rows || !s->cols || !s->w || !s->mom || !s->grad)
+    return sm_fail(ctx, SM_EINVAL, "step: bad pointer or size");
+  if (!(s->beta >= 0.f && s->beta < 1.f)) return sm_fail(ctx, SM_EINVAL, "step: beta must be in [0, 1)");
+  if (s->ns_steps < 0 || s->local_polar_steps < 0) return sm_fail(ctx, SM_EINVAL, "step: negative step count");
+  if (bad_coeffs(s->coeffs)) return sm_fail(ctx, SM_EINVAL, "step: bad coeffs");
+  if (s->scale != SM_SCALE_FRO && s->scale != SM_SCALE_SPECTRAL && s->scale != SM_SCALE_NONE)
+    return sm_fail(ctx, SM_EINVAL, "step: bad scale");
+  if (s->sign_fmt != SM_SIGN_1BIT && s->sign_fmt != SM_SIGN_INT8) return sm_fail(ctx, SM_EINVAL, "step: bad sign_fmt");
+  if (!(s->eps >= 0.f)) return sm_fail(ctx, SM_EINVAL, "step: eps must be >= 0");
+  const bool spectral = (s->scale == SM_SCALE_SPECTRAL);
+  if (spectral && (!s->v0 || s->power_iters < 0)) return sm_fail(ctx, SM_EINVAL, "step: spectral scale needs v0");
+  const int n = s->n_mats, M = s->M;
+  for (int i = 0; i < n; ++i) {
+    if (s->rows[i] < 1 || s->cols[i] < 1) return sm_fail(ctx, SM_EINVAL, "step: bad block shape");
+    if (!s->w[i] || !s->mom[i] || !s->grad[i]) return sm_fail(ctx, SM_EINVAL, "step: NULL block pointer");
+    if (!sm_aligned(s->w[i], 16) || !sm_aligned(s->mom[i], 16) || !sm_aligned(s->grad[i], 16))
+      return sm_fail(ctx, SM_EINVAL, "step: block pointers need 16-byte alignment");
+    if (spectral && !s->v0[i]) return sm_fail(ctx, SM_EINVAL, "step: NULL v0 entry");
+    if (s->signs_out && s->signs_out[i] && !sm_aligned(s->signs_out[i], 16))
+      return sm_fail(ctx, SM_EINVAL, "step: signs_out needs 16-byte alignment");
+    if (s->counts_out && s->counts_out[i] && !sm_aligned(s->counts_out[i], 16))
+      return sm_fail(ctx, SM_EINVAL, "step: counts_out needs 16-byte alignment");
+  }
+  ns_plan* pl = nullptr;
+  int rc = get_plan(ctx, n, s->rows, s->cols, M, s->coeffs[2] != 0.f, s->sign_fmt, &pl);
+  if (rc != SM_OK) return rc;
+
+  // a1: momentum for every block and worker, with the bf16 working copy and the sums of squares
+  std::vector<sm_mom_desc> descs(n);
+  for (int i = 0; i < n; ++i) {
+    ns_class& cl = pl->classes[pl->class_of[i]];
+    const int idx = pl->index_in_class[i];
+    sm_mom_desc& D = descs[i];
+    D.mom = s->mom[i];
+    D.grad = s->grad[i];
+    D.w = (s->weight_decay != 0.f) ? s->w[i] : nullptr;
+    D.x = at<bf16_t>(ctx, cl.off_x[0]) + (long long)idx * M * cl.mat;
+    D.partial = at<float>(ctx, cl.off_partial) + (long long)idx * M * cl.chunks;
+    D.d = (long long)cl.rows * cl.cols;
+    D.x_stride = cl.mat;
+    D.cols = cl.cols;
+    D.ld = cl.cp;
+    D.chunks = cl.chunks;
+    D.block_begin = 0;
+  }
+  rc = sm_launch_momentum(ctx, descs.data(), n, M, s->beta, s->weight_decay);
+  if (rc != SM_OK) return rc;
+
+  // a2: sigma per (block, worker)
+  bool use_scale = false;
+  if (s->ns_steps > 0 || (s->u_out != nullptr)) {
+    if (s->scale == SM_SCALE_FRO) {
+      for (auto& cl : pl->classes) {
+        rc = sm_launch_reduce_partials(ctx, at<float>(ctx, cl.off_partial), cl.chunks, cl.count * M,
+                                       at<float>(ctx, cl.off_sig));
+        if (rc != SM_OK) return rc;
+        rc = sm_launch_inv_sigma(ctx, at<float>(ctx, cl.off_sig), cl.count * M, s->eps, true, at<float>(ctx, cl.off_inv));
+        if (rc != SM_OK) return rc;
+      }
+      use_scale = true;
+    } else if (spectral) {
+      for (int i = 0; i < n; ++i) {
+        ns_class& cl = pl->classes[pl->class_of[i]];
+        const long long first = (long long)pl->index_in_class[i] * M;
+        rc = sm_launch_power_iter(ctx, at<bf16_t>(ctx, cl.off_x[0]) + first * cl.mat, cl.rows, cl.cols, cl.cp, cl.mat,
+                                  M, s->power_iters, s->eps, s->v0[i], cl.cols, at<float>(ctx, pl->off_pi),
+                                  at<float>(ctx, cl.off_sig) + first);
+        if (rc != SM_OK) return rc;
+      }
+      for (auto& cl : pl->classes) {
+        rc = sm_launch_inv_sigma(ctx, at<float>(ctx, cl.off_sig), cl.count * M, s->eps, false, at<float>(ctx, cl.off_inv));
+        if (rc != SM_OK) return rc;
+      }
+      use_scale = true;
+    }
+  }
+
+  // a3 + a4: K Newton-Schulz steps on all (block, worker) matrices
+  int cur = 0;
+  rc = run_ns(ctx, pl, M, s->ns_steps, s->coeffs, use_scale, &cur);
+  if (rc != SM_OK) return rc;
+
+  const int Kp = s->local_polar_steps;
+  for (int i = 0; i < n; ++i) {
+    ns_class& cl = pl->classes[pl->class_of[i]];
+    const int idx = pl->index_in_class[i];
+    const long long d = (long long)cl.rows * cl.cols;
+    const bf16_t* u = at<bf16_t>(ctx, cl.off_x[cur]) + (long long)idx * M * cl.mat;
+    if (s->u_out && s->u_out[i]) {
+      rc = sm_launch_copy_out(ctx, u, cl.cp, cl.mat, M, cl.rows, cl.cols, s->u_out[i], SM_BF16,
+                              (s->ns_steps == 0 && use_scale) ? at<float>(ctx, cl.off_inv) + (long long)idx * M : nullptr);
+      if (rc != SM_OK) return rc;
+    }
+    // a5: sign + pack
+    void* signs = (s->signs_out && s->signs_out[i]) ? s->signs_out[i] : at<void>(ctx, pl->off_signs[i]);
+    const long long stride = (s->signs_out && s->signs_out[i])
+                                 ? ((s->sign_fmt == SM_SIGN_INT8) ? d : 8 * ((d + 63) / 64))
+                                 : pl->sign_stride[i];
+    rc = sm_launch_sign_pack(ctx, u, SM_BF16, M, cl.rows, cl.cols, cl.cp, cl.mat, s->sign_fmt, signs, stride);
+    if (rc != SM_OK) return rc;
+    // a6 (+ a8 when there is no local polar step)
+    float step = s->lr;
+    if (s->update_rsqrt_mn) step = s->lr / sqrtf((float)cl.rows * (float)cl.cols);
+    sm_vote_args v;
+    v.signs = signs;
+    v.fmt = s->sign_fmt;
+    v.M = M;
+    v.n = d;
+    v.stride_bytes = stride;
+    v.counts = (s->counts_out) ? s->counts_out[i] : nullptr;
+    v.lr_scaled = step;
+    if (Kp == 0) {
+      v.voted = nullptr;
+      v.vfmt = SM_VOTE_BITS;
+      v.cols = v.ld = 1;
+      v.w = s->w[i];
+    } else {
+      // the voted +-1 matrix becomes item `idx` of the class's post-vote batch, in the
+      // buffer that does not hold the workers' U
+      v.voted = at<bf16_t>(ctx, cl.off_x[cur ^ 1]) + (long long)idx * cl.mat;
+      v.vfmt = SM_VOTE_BF16;
+      v.cols = cl.cols;
+      v.ld = cl.cp;
+      v.w = nullptr;
+    }
+    rc = sm_launch_vote(ctx, v);
+    if (rc != SM_OK) return rc;
+    if (Kp == 0 && s->d_out && s->d_out[i]) {
+      sm_vote_args t = v;
+      t.voted = s->d_out[i];
+      t.vfmt = SM_VOTE_BF16;
+      t.cols = t.ld = 1;
+      t.counts = nullptr;
+      t.w = nullptr;
+      // W was already stepped; the tap only re-derives the vote
+      rc = sm_launch_vote(ctx, t);
+      if (rc != SM_OK) return rc;
+    }
+  }
+  if (Kp == 0) return SM_OK;
+
+  // a7: local polar step on the voted sign matrices (one per block)
+  bool use_scale2 = false;
+  if (s->scale == SM_SCALE_FRO) {
+    for (auto& cl : pl->classes) {
+      // every entry is +-1, so the Frobenius norm is exactly sqrt(rows*cols)
+      const float sig = sqrtf((float)cl.rows * (float)cl.cols);
+      rc = sm_launch_fill(ctx, at<float>(ctx, cl.off_inv), cl.count, 1.0f / fmaxf(sig, s->eps));
+      if (rc != SM_OK) return rc;
+    }
+    use_scale2 = true;
+  } else if (spectral) {
+    for (int i = 0; i < n; ++i) {
+      ns_class& cl = pl->classes[pl->class_of[i]];
+      const int idx = pl->index_in_class[i];
+      rc = sm_launch_power_iter(ctx, at<bf16_t>(ctx, cl.off_x[cur ^ 1]) + (long long)idx * cl.mat, cl.rows, cl.cols, cl.cp,
+                                cl.mat, 1, s->power_iters, s->eps, s->v0[i], cl.cols, at<float>(ctx, pl->off_pi),
+                                at<float>(ctx, cl.off_sig) + idx);
+      if (rc != SM_OK) return rc;
+    }
+    for (auto& cl : pl->classes) {
+      rc = sm_launch_inv_sigma(ctx, at<float>(ctx, cl.off_sig), cl.count, s->eps, false, at<float>(ctx, cl.off_inv));
+      if (rc != SM_OK) return rc;
+    }
+    use_scale2 = true;
+  }
+  cur ^= 1;
+  rc = run_ns(ctx, pl, 1, Kp, s->coeffs, use_scale2, &cur);
+  if (rc != SM_OK) return rc;
+
+  // a8: W <- W - step * D
+  for (int i = 0; i < n; ++i) {
+    ns_class& cl = pl->classes[pl->class_of[i]];
+    const int idx = pl->index_in_class[i];
+    const bf16_t* dmat = at<bf16_t>(ctx, cl.off_x[cur]) + (long long)idx * cl.mat;
+    float step = s->lr;
+    if (s->update_rsqrt_mn) step = s->lr / sqrtf((float)cl.rows * (float)cl.cols);
+    rc = sm_launch_update(ctx, s->w[i], dmat, cl.rows, cl.cols, cl.cp, step);
+    if (rc != SM_OK) return rc;
+    if (s->d_out && s->d_out[i]) {
+      rc = sm_launch_copy_out(ctx, dmat, cl.cp, cl.mat, 1, cl.rows, cl.cols, s->d_out[i], SM_BF16, nullptr);
+      if (rc != SM_OK) return rc;
+    }
+  }
+  return SM_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,160 @@
+// Internal declarations shared by the HIP sources of libsignmuon (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "../../include/signmuon.h"
+
+typedef __bf16 bf16_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+
+// ---------------------------------------------------------------- context
+struct sm_event_pair {
+  hipEvent_t a, b;
+};
+
+struct signmuon_ctx {
+  hipStream_t stream = nullptr;
+  int device = 0;
+  std::string last_error;
+
+  // one growable device arena; sub-allocated by the NS plan (see plan.hip)
+  void* arena = nullptr;
+  size_t arena_bytes = 0;
+
+  // cached NS plan (shape classes + workspace offsets)
+  struct ns_plan* plan = nullptr;
+
+  // timing taps
+  bool profiling = false;
+  std::vector<sm_event_pair> ev_pool;        // every pair ever created
+  size_t ev_used = 0;                        // pairs handed out since the last reset
+  std::vector<std::pair<int, size_t>> ev_log;  // (kernel class, pool index)
+};
+
+int sm_fail(signmuon_ctx* ctx, int code, const std::string& msg);
+int sm_hip_fail(signmuon_ctx* ctx, hipError_t e, const char* what);
+
+#define SM_HIP(ctx, call)                                        \
+  do {                                                           \
+    hipError_t e__ = (call);                                     \
+    if (e__ != hipSuccess) return sm_hip_fail(ctx, e__, #call);  \
+  } while (0)
+
+// Scoped launch bracket: records an event pair around a launch when profiling.
+struct sm_launch_scope {
+  signmuon_ctx* ctx;
+  int klass;
+  long idx = -1;
+  sm_launch_scope(signmuon_ctx* c, int k);
+  ~sm_launch_scope();
+};
+
+// Ensures the arena holds at least `bytes`; contents are lost when it grows.
+int sm_arena_reserve(signmuon_ctx* ctx, size_t bytes);
+
+static inline int64_t sm_round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+static inline bool sm_aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// ---------------------------------------------------------------- streaming kernels (stream.hip)
+// Descriptor of one weight block for the grouped momentum launch.
+struct sm_mom_desc {
+  float* mom;          // [M][d]
+  const float* grad;   // [M][d]
+  const float* w;      // [d] or null
+  bf16_t* x;           // [M][rows_p][ld] padded bf16 copy, or null
+  float* partial;      // [M][chunks] per-chunk sums of squares, or null
+  long long d;         // rows*cols
+  long long x_stride;  // elements between workers in x
+  int cols, ld;        // logical row length and padded row length of x
+  int chunks;          // chunks per worker
+  int block_begin;     // first workgroup of this block in the grouped launch
+};
+constexpr int SM_MOM_MAX_GROUP = 40;
+constexpr int SM_MOM_CHUNK = 8192;  // elements per workgroup
+
+int sm_launch_momentum(signmuon_ctx* ctx, const sm_mom_desc* descs, int n, int M, float beta, float wd);
+// sumsq[i] = sum_j partial[i*chunks + j], i < count (fixed order)
+int sm_launch_reduce_partials(signmuon_ctx* ctx, const float* partial, int chunks, int count, float* sumsq);
+// inv_sigma[i] = 1 / max(sqrt(sumsq[i]), eps)   (from_sq) or 1 / max(sumsq[i], eps)
+int sm_launch_inv_sigma(signmuon_ctx* ctx, const float* sig, int count, float eps, bool from_sq, float* inv_sigma);
+
+// sign pack from a (possibly padded) 2-D source: u[batch][rows][ld] -> flat row-major bits
+int sm_launch_sign_pack(signmuon_ctx* ctx, const void* u, int dtype, int batch, int rows, int cols,
+                        int ld, long long batch_stride, int fmt, void* out, long long out_stride_bytes);
+
+struct sm_vote_args {
+  const void* signs;
+  int fmt, M;
+  long long n, stride_bytes;
+  void* voted;
+  int vfmt;          // SM_VOTE_*; for BF16/F32 the destination may be 2-D padded:
+  int cols, ld;      // voted element i goes to (i / cols) * ld + (i % cols); ld == cols: flat
+  int32_t* counts;
+  float* w;
+  float lr_scaled;
+};
+int sm_launch_vote(signmuon_ctx* ctx, const sm_vote_args& a);
+
+// w[r][c] -= step * d[r][ld] (bf16 d)
+int sm_launch_update(signmuon_ctx* ctx, float* w, const bf16_t* d, int rows, int cols, int ld, float step);
+
+// ---------------------------------------------------------------- layout helpers (layout.hip)
+// dst[b][rows_p][ld] (bf16, padding untouched) <- src[b][rows][cols] (f32 or bf16)
+int sm_launch_copy_in(signmuon_ctx* ctx, const void* src, int dtype, int batch, int rows, int cols,
+                      bf16_t* dst, int ld, long long dst_stride);
+// dst[b][rows][cols] (f32 or bf16) <- scale[b] * src[b][rows][ld]; scale may be null
+int sm_launch_copy_out(signmuon_ctx* ctx, const bf16_t* src, int ld, long long src_stride, int batch, int rows,
+                       int cols, void* dst, int dtype, const float* scale);
+// dst[b][C][ldd] <- transpose(src[b][R][lds]) for bf16, R and C multiples of 64
+int sm_launch_transpose(signmuon_ctx* ctx, const bf16_t* src, int R, int C, int lds, long long sstride,
+                        bf16_t* dst, int ldd, long long dstride, int batch);
+// sumsq[b] = sum of squares of x[b][0..n) (f32 or bf16; two stages, fixed order);
+// scratch: batch * ceil(n / SM_MOM_CHUNK) floats
+int sm_launch_sumsq(signmuon_ctx* ctx, const void* x, int dtype, long long n_per_batch, int batch, float* scratch,
+                    float* sumsq);
+
+// ---------------------------------------------------------------- GEMM (ns_gemm.hip)
+// C[b] = alpha * scale[b]^scale_pow * (A[b] * B[b]^T) + gamma * R[b] + diag * I
+// A: [M][lda], B: [N][ldb] (both K-contiguous), C, R: [M][ldc]; M, N, K multiples of 64.
+struct sm_gemm_prob {
+  const bf16_t* A;
+  const bf16_t* B;
+  bf16_t* C;
+  const bf16_t* R;       // or null
+  const float* scale;    // [batch] or null
+  long long sA, sB, sC;  // batch strides in elements
+  int M, N, K;
+  int lda, ldb, ldc;
+  int batch;
+  int tiles_m, tiles_n;
+  int tile_begin;
+  int pad_;
+};
+constexpr int SM_GEMM_MAX_PROB = 32;
+struct sm_gemm_args {
+  int n_prob;
+  int total_tiles;
+  int tiles_per_xcd;
+  int scale_pow;  // 0, 1 or 2
+  float alpha, gamma, diag;
+  int pad_;
+  sm_gemm_prob p[SM_GEMM_MAX_PROB];
+};
+// Fills tiles_m/tiles_n/tile_begin/total_tiles and launches; klass is SM_K_NS_GRAM or SM_K_NS_APPLY.
+int sm_launch_gemm_nt(signmuon_ctx* ctx, sm_gemm_args& args, int klass);
+
+// ---------------------------------------------------------------- power iteration (poweriter.hip)
+// sigma[b] = PowerIter(X[b], P, eps, v0[b]); X bf16 [rows][ld]; scratch: (rows + 2*cols + 4) floats per batch
+int sm_launch_power_iter(signmuon_ctx* ctx, const bf16_t* x, int rows, int cols, int ld, long long stride,
+                         int batch, int P, float eps, const float* v0, long long v0_stride, float* scratch,
+                         float* sigma);

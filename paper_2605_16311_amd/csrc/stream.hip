@@ -1,0 +1,560 @@
+// HBM-bound kernels of the Sign-Muon step: momentum (a1), sign extraction and
+// packing (a5), majority vote (a6) with the fused update (a8), and the update
+// after a local polar step.  All are pure streaming passes: every byte is read
+// once with 16-byte (or 4-byte broadcast) coalesced accesses and written once.
+#include "common.h"
+
+namespace {
+
+constexpr int TPB = 256;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+  return v;
+}
+
+// Sum over the 256 threads of a workgroup, fixed order; result valid in thread 0.
+__device__ __forceinline__ float block_sum(float v, float* lds4) {
+  v = wave_sum(v);
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  if (lane == 0) lds4[wv] = v;
+  __syncthreads();
+  float r = 0.f;
+  if (threadIdx.x == 0) r = (lds4[0] + lds4[1]) + (lds4[2] + lds4[3]);
+  return r;
+}
+
+// sign decision of Alg. 3's encoding note, x >= 0 by IEEE comparison, taken on
+// the bit pattern so that it does not depend on the denormal mode:
+// true for +0 .. +inf and for -0, false for negatives and every NaN.
+__device__ __forceinline__ unsigned ge0_f32(unsigned u) { return (u <= 0x7F800000u) | (u == 0x80000000u); }
+__device__ __forceinline__ unsigned ge0_bf16(unsigned h) { return (h <= 0x7F80u) | (h == 0x8000u); }
+
+// ------------------------------------------------------------------ momentum
+struct mom_args {
+  int n, M;
+  float beta, omb, wd;
+  int pad_;
+  sm_mom_desc d[SM_MOM_MAX_GROUP];
+};
+
+__device__ __forceinline__ float mom_one(float m, float g, float w, const mom_args& a, bool has_wd) {
+  if (has_wd) g = __fadd_rn(g, __fmul_rn(a.wd, w));
+  return __fadd_rn(__fmul_rn(a.beta, m), __fmul_rn(a.omb, g));
+}
+
+template <bool VEC>
+__global__ void __launch_bounds__(TPB) sm_momentum_kernel(const mom_args a) {
+  __shared__ float red[4];
+  int bi = 0;
+  while (bi + 1 < a.n && (int)blockIdx.x >= a.d[bi + 1].block_begin) ++bi;
+  const sm_mom_desc& D = a.d[bi];
+  const int local = blockIdx.x - D.block_begin;
+  const int p = local / D.chunks, ch = local - p * D.chunks;
+  const long long d = D.d;
+  float* mom = D.mom + (long long)p * d;
+  const float* grad = D.grad + (long long)p * d;
+  const float* w = D.w;
+  bf16_t* x = D.x ? D.x + (long long)p * D.x_stride : nullptr;
+  const bool has_wd = (w != nullptr) && (a.wd != 0.f);
+  const bool flat = (D.ld == D.cols);
+  const long long base = (long long)ch * SM_MOM_CHUNK;
+  float ss = 0.f;
+  if (VEC) {
+#pragma unroll
+    for (int it = 0; it < SM_MOM_CHUNK / (TPB * 4); ++it) {
+      const long long i = base + (long long)it * (TPB * 4) + threadIdx.x * 4;
+      if (i >= d) break;  // d % 4 == 0 on this path
+      f32x4 m = *reinterpret_cast<const f32x4*>(mom + i);
+      const f32x4 g = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(grad + i));
+      f32x4 ww = {0.f, 0.f, 0.f, 0.f};
+      if (has_wd) ww = *reinterpret_cast<const f32x4*>(w + i);
+      m.x = mom_one(m.x, g.x, ww.x, a, has_wd);
+      m.y = mom_one(m.y, g.y, ww.y, a, has_wd);
+      m.z = mom_one(m.z, g.z, ww.z, a, has_wd);
+      m.w = mom_one(m.w, g.w, ww.w, a, has_wd);
+      *reinterpret_cast<f32x4*>(mom + i) = m;
+      ss += (m.x * m.x + m.y * m.y) + (m.z * m.z + m.w * m.w);
+      if (x) {
+        if (flat || (D.cols & 3) == 0) {
+          const long long xi = flat ? i : (i / D.cols) * D.ld + (i % D.cols);
+          bf16x4 h = {(bf16_t)m.x, (bf16_t)m.y, (bf16_t)m.z, (bf16_t)m.w};
+          *reinterpret_cast<bf16x4*>(x + xi) = h;
+        } else {
+          const float mv[4] = {m.x, m.y, m.z, m.w};
+          for (int k = 0; k < 4; ++k) {
+            const long long e = i + k;
+            x[(e / D.cols) * D.ld + (e % D.cols)] = (bf16_t)mv[k];
+          }
+        }
+      }
+    }
+  } else {
+    for (int it = 0; it < SM_MOM_CHUNK / TPB; ++it) {
+      const long long i = base + (long long)it * TPB + threadIdx.x;
+      if (i >= d) break;
+      const float m = mom_one(mom[i], grad[i], has_wd ? w[i] : 0.f, a, has_wd);
+      mom[i] = m;
+      ss += m * m;
+      if (x) x[flat ? i : (i / D.cols) * D.ld + (i % D.cols)] = (bf16_t)m;
+    }
+  }
+  if (D.partial) {
+    const float tot = block_sum(ss, red);
+    if (threadIdx.x == 0) D.partial[(long long)p * D.chunks + ch] = tot;
+  }
+}
+
+// sumsq[i] = sum of partial[i*chunks .. +chunks) in a fixed tree order; one workgroup per i.
+__global__ void __launch_bounds__(TPB) sm_reduce_partials_kernel(const float* partial, int chunks, float* sumsq) {
+  __shared__ float red[4];
+  const float* src = partial + (long long)blockIdx.x * chunks;
+  float s = 0.f;
+  for (int j = threadIdx.x; j < chunks; j += TPB) s += src[j];
+  const float tot = block_sum(s, red);
+  if (threadIdx.x == 0) sumsq[blockIdx.x] = tot;
+}
+
+__global__ void sm_inv_sigma_kernel(const float* sig, int count, float eps, int from_sq, float* inv) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= count) return;
+  float s = sig[i];
+  if (from_sq) s = sqrtf(s);
+  inv[i] = 1.0f / fmaxf(s, eps);
+}
+
+__global__ void sm_fill_kernel(float* p, int n, float v) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// ------------------------------------------------------------------ sign pack
+// One thread = one output byte = 8 consecutive entries of the flattened matrix.
+// Source row index / padded leading dimension are resolved per byte (cols % 8 == 0
+// on the fast path so a byte never straddles rows).
+template <int DT, int FMT, bool FAST>
+__global__ void __launch_bounds__(TPB) sm_sign_pack_kernel(const void* __restrict__ u, long long n, int cols, int ld,
+                                                           long long batch_stride, void* __restrict__ out,
+                                                           long long out_stride, long long bytes_per_row) {
+  const int b = blockIdx.y;
+  const unsigned short* ub = reinterpret_cast<const unsigned short*>(u) + (DT == SM_BF16 ? (long long)b * batch_stride : 0);
+  const unsigned* uf = reinterpret_cast<const unsigned*>(u) + (DT == SM_F32 ? (long long)b * batch_stride : 0);
+  unsigned char* o = reinterpret_cast<unsigned char*>(out) + (long long)b * out_stride;
+  constexpr int UNROLL = 4;
+  const long long q0 = ((long long)blockIdx.x * UNROLL) * TPB + threadIdx.x;
+#pragma unroll
+  for (int j = 0; j < UNROLL; ++j) {
+    const long long q = q0 + (long long)j * TPB;  // byte index
+    if (q >= bytes_per_row) break;
+    const long long e0 = q * 8;
+    unsigned bits = 0;
+    if (FAST && e0 + 8 <= n) {
+      const long long src = (ld == cols) ? e0 : (e0 / cols) * ld + (e0 % cols);
+      if (DT == SM_BF16) {
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ub + src));
+        const unsigned wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          bits |= ge0_bf16(wv[k] & 0xFFFFu) << (2 * k);
+          bits |= ge0_bf16(wv[k] >> 16) << (2 * k + 1);
+        }
+      } else {
+        const u32x4 v0 = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(uf + src));
+        const u32x4 v1 = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(uf + src + 4));
+        const unsigned wv[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+        for (int k = 0; k < 8; ++k) bits |= ge0_f32(wv[k]) << k;
+      }
+      if (FMT == SM_SIGN_INT8) {
+        // +1 = 0x01, -1 = 0xFF
+        unsigned lo = 0, hi = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          lo |= (((bits >> k) & 1u) ? 0x01u : 0xFFu) << (8 * k);
+          hi |= (((bits >> (k + 4)) & 1u) ? 0x01u : 0xFFu) << (8 * k);
+        }
+        *reinterpret_cast<uint2*>(o + e0) = make_uint2(lo, hi);
+        continue;
+      }
+    } else {
+      for (int k = 0; k < 8; ++k) {
+        const long long e = e0 + k;
+        if (e >= n) break;
+        const long long src = (ld == cols) ? e : (e / cols) * ld + (e % cols);
+        const unsigned g = (DT == SM_BF16) ? ge0_bf16(ub[src]) : ge0_f32(uf[src]);
+        bits |= g << k;
+        if (FMT == SM_SIGN_INT8) o[e] = g ? 0x01 : 0xFF;
+      }
+      if (FMT == SM_SIGN_INT8) continue;
+    }
+    o[q] = (unsigned char)bits;
+  }
+}
+
+// ------------------------------------------------------------------ vote
+// Voted bits only: one thread = one 64-bit word.  Bit-sliced counting: the M
+// words are added into PLANES binary counter planes with ripple carries
+// (M < 2^PLANES), then the planes are compared with the threshold ceil(M/2)
+// bit-serially from the top plane down.
+template <int PLANES>
+__global__ void __launch_bounds__(TPB) sm_vote_bits_kernel(const unsigned long long* __restrict__ signs, int M,
+                                                           long long words, long long stride_words,
+                                                           long long n, unsigned long long* __restrict__ voted) {
+  const long long wi = (long long)blockIdx.x * TPB + threadIdx.x;
+  if (wi >= words) return;
+  unsigned long long plane[PLANES];
+#pragma unroll
+  for (int k = 0; k < PLANES; ++k) plane[k] = 0;
+  for (int p = 0; p < M; ++p) {
+    unsigned long long carry = __builtin_nontemporal_load(signs + (long long)p * stride_words + wi);
+#pragma unroll
+    for (int k = 0; k < PLANES; ++k) {
+      const unsigned long long t = plane[k] & carry;
+      plane[k] ^= carry;
+      carry = t;
+    }
+  }
+  const unsigned T = (unsigned)((M + 1) / 2);  // vote = (count >= T)
+  unsigned long long gt = 0, eq = ~0ull;
+#pragma unroll
+  for (int k = PLANES - 1; k >= 0; --k) {
+    const unsigned long long tb = ((T >> k) & 1u) ? ~0ull : 0ull;
+    gt |= eq & plane[k] & ~tb;
+    eq &= ~(plane[k] ^ tb);
+  }
+  unsigned long long v = gt | eq;
+  const long long rem = n - wi * 64;
+  if (rem < 64) v &= (rem <= 0) ? 0ull : ((1ull << rem) - 1ull);
+  voted[wi] = v;
+}
+
+// Voted bits for any M (used beyond 255 workers): one thread = one byte.
+__global__ void __launch_bounds__(TPB) sm_vote_bits_generic_kernel(const unsigned char* __restrict__ signs, int M,
+                                                                   long long n, long long stride_bytes,
+                                                                   unsigned char* __restrict__ voted,
+                                                                   long long bytes_out) {
+  const long long q = (long long)blockIdx.x * TPB + threadIdx.x;
+  if (q >= bytes_out) return;
+  int c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int p = 0; p < M; ++p) {
+    const unsigned b = signs[(long long)p * stride_bytes + q];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) c[k] += (b >> k) & 1u;
+  }
+  unsigned bits = 0;
+#pragma unroll
+  for (int k = 0; k < 8; ++k)
+    if (q * 8 + k < n && 2 * c[k] >= M) bits |= 1u << k;
+  voted[q] = (unsigned char)bits;
+}
+
+struct vote_x_args {
+  const void* signs;
+  long long n, stride_bytes;
+  void* voted;
+  int32_t* counts;
+  float* w;
+  float lr;
+  int M, vfmt, cols, ld;
+};
+
+// Expanding vote: one thread = 4 consecutive entries.  FMT selects the input
+// transport; outputs (voted in a non-bit format, counts, fused W update) are all
+// optional.  n4 = ceil(n/4) threads in total.
+template <int FMT>
+__global__ void __launch_bounds__(TPB) sm_vote_expand_kernel(const vote_x_args a) {
+  const long long t = (long long)blockIdx.x * TPB + threadIdx.x;
+  const long long e0 = t * 4;
+  if (e0 >= a.n) return;
+  int c[4] = {0, 0, 0, 0};
+  if (FMT == SM_SIGN_1BIT) {
+    const unsigned* base = reinterpret_cast<const unsigned*>(a.signs) + (e0 >> 5);
+    const int sh = (int)(e0 & 31);
+    const long long stride_w = a.stride_bytes >> 2;
+    int p = 0;
+    while (p < a.M) {
+      const int lim = min(a.M, p + 255);
+      unsigned acc = 0;
+      for (; p < lim; ++p) {
+        const unsigned nib = (base[(long long)p * stride_w] >> sh) & 0xFu;
+        acc += (nib * 0x00204081u) & 0x01010101u;
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) c[k] += (acc >> (8 * k)) & 0xFF;
+    }
+  } else {
+    const signed char* base = reinterpret_cast<const signed char*>(a.signs) + e0;
+    if (e0 + 4 <= a.n && (a.stride_bytes & 3) == 0 && (reinterpret_cast<uintptr_t>(a.signs) & 3) == 0) {
+      for (int p = 0; p < a.M; ++p) {
+        const unsigned v = __builtin_nontemporal_load(reinterpret_cast<const unsigned*>(base + (long long)p * a.stride_bytes));
+#pragma unroll
+        for (int k = 0; k < 4; ++k) c[k] += (int)(signed char)(v >> (8 * k));
+      }
+    } else {
+      for (int p = 0; p < a.M; ++p)
+        for (int k = 0; k < 4; ++k)
+          if (e0 + k < a.n) c[k] += base[(long long)p * a.stride_bytes + k];
+    }
+  }
+  float s[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const bool plus = (FMT == SM_SIGN_1BIT) ? (2 * c[k] >= a.M) : (c[k] >= 0);
+    s[k] = plus ? 1.0f : -1.0f;
+  }
+  const bool full = (e0 + 4 <= a.n);
+  if (a.counts) {
+    if (full) {
+      *reinterpret_cast<int4*>(a.counts + e0) = make_int4(c[0], c[1], c[2], c[3]);
+    } else {
+      for (int k = 0; k < 4 && e0 + k < a.n; ++k) a.counts[e0 + k] = c[k];
+    }
+  }
+  if (a.w) {
+    if (full) {
+      float4 wv = *reinterpret_cast<float4*>(a.w + e0);
+      wv.x = __fsub_rn(wv.x, __fmul_rn(a.lr, s[0]));
+      wv.y = __fsub_rn(wv.y, __fmul_rn(a.lr, s[1]));
+      wv.z = __fsub_rn(wv.z, __fmul_rn(a.lr, s[2]));
+      wv.w = __fsub_rn(wv.w, __fmul_rn(a.lr, s[3]));
+      *reinterpret_cast<float4*>(a.w + e0) = wv;
+    } else {
+      for (int k = 0; k < 4 && e0 + k < a.n; ++k) a.w[e0 + k] = __fsub_rn(a.w[e0 + k], __fmul_rn(a.lr, s[k]));
+    }
+  }
+  if (a.voted) {
+    const bool flat = (a.ld == a.cols);
+    if (a.vfmt == SM_VOTE_INT8) {
+      signed char* o = reinterpret_cast<signed char*>(a.voted);
+      if (full) {
+        unsigned v = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v |= (s[k] > 0.f ? 0x01u : 0xFFu) << (8 * k);
+        *reinterpret_cast<unsigned*>(o + e0) = v;
+      } else {
+        for (int k = 0; k < 4 && e0 + k < a.n; ++k) o[e0 + k] = s[k] > 0.f ? 1 : -1;
+      }
+    } else if (a.vfmt == SM_VOTE_BF16) {
+      bf16_t* o = reinterpret_cast<bf16_t*>(a.voted);
+      if (full && (flat || (a.cols & 3) == 0)) {
+        const long long di = flat ? e0 : (e0 / a.cols) * a.ld + (e0 % a.cols);
+        bf16x4 h = {(bf16_t)s[0], (bf16_t)s[1], (bf16_t)s[2], (bf16_t)s[3]};
+        *reinterpret_cast<bf16x4*>(o + di) = h;
+      } else {
+        for (int k = 0; k < 4 && e0 + k < a.n; ++k) {
+          const long long e = e0 + k;
+          o[flat ? e : (e / a.cols) * a.ld + (e % a.cols)] = (bf16_t)s[k];
+        }
+      }
+    } else if (a.vfmt == SM_VOTE_F32) {
+      float* o = reinterpret_cast<float*>(a.voted);
+      if (full && (flat || (a.cols & 3) == 0)) {
+        const long long di = flat ? e0 : (e0 / a.cols) * a.ld + (e0 % a.cols);
+        *reinterpret_cast<float4*>(o + di) = make_float4(s[0], s[1], s[2], s[3]);
+      } else {
+        for (int k = 0; k < 4 && e0 + k < a.n; ++k) {
+          const long long e = e0 + k;
+          o[flat ? e : (e / a.cols) * a.ld + (e % a.cols)] = s[k];
+        }
+      }
+    }
+  }
+}
+
+// Packs +-1 int32 sums (int8 transport) into voted bits: one thread = one byte.
+__global__ void __launch_bounds__(TPB) sm_vote_int8_bits_kernel(const signed char* __restrict__ signs, int M,
+                                                                long long n, long long stride_bytes,
+                                                                unsigned char* __restrict__ voted,
+                                                                long long bytes_out) {
+  const long long q = (long long)blockIdx.x * TPB + threadIdx.x;
+  if (q >= bytes_out) return;
+  unsigned bits = 0;
+  for (int k = 0; k < 8; ++k) {
+    const long long e = q * 8 + k;
+    if (e >= n) break;
+    int s = 0;
+    for (int p = 0; p < M; ++p) s += signs[(long long)p * stride_bytes + e];
+    bits |= (s >= 0 ? 1u : 0u) << k;
+  }
+  voted[q] = (unsigned char)bits;
+}
+
+// ------------------------------------------------------------------ update after a local polar step
+__global__ void __launch_bounds__(TPB) sm_update_kernel(float* __restrict__ w, const bf16_t* __restrict__ d, int rows,
+                                                        int cols, int ld, float step) {
+  const long long n = (long long)rows * cols;
+  const long long e0 = ((long long)blockIdx.x * TPB + threadIdx.x) * 4;
+  if (e0 >= n) return;
+  if (e0 + 4 <= n && (cols & 3) == 0) {
+    const long long di = (ld == cols) ? e0 : (e0 / cols) * ld + (e0 % cols);
+    const bf16x4 h = *reinterpret_cast<const bf16x4*>(d + di);
+    float4 wv = *reinterpret_cast<float4*>(w + e0);
+    wv.x = __fsub_rn(wv.x, __fmul_rn(step, (float)h[0]));
+    wv.y = __fsub_rn(wv.y, __fmul_rn(step, (float)h[1]));
+    wv.z = __fsub_rn(wv.z, __fmul_rn(step, (float)h[2]));
+    wv.w = __fsub_rn(wv.w, __fmul_rn(step, (float)h[3]));
+    *reinterpret_cast<float4*>(w + e0) = wv;
+  } else {
+    for (int k = 0; k < 4 && e0 + k < n; ++k) {
+      const long long e = e0 + k;
+      const float dv = (float)d[(e / cols) * ld + (e % cols)];
+      w[e] = __fsub_rn(w[e], __fmul_rn(step, dv));
+    }
+  }
+}
+
+}  // namespace
+
+// =================================================================== host side
+int sm_launch_momentum(signmuon_ctx* ctx, const sm_mom_desc* descs, int n, int M, float beta, float wd) {
+  int done = 0;
+  while (done < n) {
+    const int g = std::min(n - done, SM_MOM_MAX_GROUP);
+    mom_args a;
+    a.n = g;
+    a.M = M;
+    a.beta = beta;
+    a.omb = 1.0f - beta;
+    a.wd = wd;
+    a.pad_ = 0;
+    int blocks = 0;
+    bool vec = true;
+    for (int i = 0; i < g; ++i) {
+      a.d[i] = descs[done + i];
+      a.d[i].block_begin = blocks;
+      blocks += M * a.d[i].chunks;
+      const sm_mom_desc& D = a.d[i];
+      vec = vec && (D.d % 4 == 0) && sm_aligned(D.mom, 16) && sm_aligned(D.grad, 16) &&
+            (!D.w || sm_aligned(D.w, 16)) && (!D.x || (sm_aligned(D.x, 8) && D.ld % 4 == 0 && D.x_stride % 4 == 0));
+    }
+    {
+      sm_launch_scope sc(ctx, SM_K_MOMENTUM);
+      if (vec)
+        hipLaunchKernelGGL(sm_momentum_kernel<true>, dim3(blocks), dim3(TPB), 0, ctx->stream, a);
+      else
+        hipLaunchKernelGGL(sm_momentum_kernel<false>, dim3(blocks), dim3(TPB), 0, ctx->stream, a);
+    }
+    SM_HIP(ctx, hipGetLastError());
+    done += g;
+  }
+  return SM_OK;
+}
+
+int sm_launch_reduce_partials(signmuon_ctx* ctx, const float* partial, int chunks, int count, float* sumsq) {
+  sm_launch_scope sc(ctx, SM_K_OTHER);
+  hipLaunchKernelGGL(sm_reduce_partials_kernel, dim3(count), dim3(TPB), 0, ctx->stream, partial, chunks, sumsq);
+  SM_HIP(ctx, hipGetLastError());
+  return SM_OK;
+}
+
+int sm_launch_inv_sigma(signmuon_ctx* ctx, const float* sig, int count, float eps, bool from_sq, float* inv_sigma) {
+  sm_launch_scope sc(ctx, SM_K_OTHER);
+  hipLaunchKernelGGL(sm_inv_sigma_kernel, dim3((count + 255) / 256), dim3(256), 0, ctx->stream, sig, count, eps,
+                     from_sq ? 1 : 0, inv_sigma);
+  SM_HIP(ctx, hipGetLastError());
+  return SM_OK;
+}
+
+int sm_launch_fill(signmuon_ctx* ctx, float* p, int n, float v) {
+  sm_launch_scope sc(ctx, SM_K_OTHER);
+  hipLaunchKernelGGL(sm_fill_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, p, n, v);
+  SM_HIP(ctx, hipGetLastError());
+  return SM_OK;
+}
+
+int sm_launch_sign_pack(signmuon_ctx* ctx, const void* u, int dtype, int batch, int rows, int cols, int ld,
+                        long long batch_stride, int fmt, void* out, long long out_stride_bytes) {
+  const long long n = (long long)rows * cols;
+  const long long bytes_per_row = (fmt == SM_SIGN_1BIT) ? 8 * ((n + 63) / 64) : (n + 7) / 8;  // threads per row
+  // the fast path reads whole 8-entry groups with 16-byte loads
+  const bool fast_ok = (ld == cols || (cols % 8 == 0 && ld % 8 == 0)) && sm_aligned(u, 16) &&
+                       (batch_stride % 8 == 0) &&
+                       (fmt == SM_SIGN_1BIT || (sm_aligned(out, 8) && out_stride_bytes % 8 == 0));
+  const unsigned gx = (unsigned)((bytes_per_row + TPB * 4 - 1) / (TPB * 4));
+  dim3 grid(gx, batch);
+  sm_launch_scope sc(ctx, SM_K_SIGN_PACK);
+#define SP_LAUNCH(DT, FMT, FAST)                                                                               \
+  hipLaunchKernelGGL((sm_sign_pack_kernel<DT, FMT, FAST>), grid, dim3(TPB), 0, ctx->stream, u, n, cols, ld,     \
+                     batch_stride, out, out_stride_bytes, bytes_per_row)
+  if (dtype == SM_BF16) {
+    if (fmt == SM_SIGN_1BIT) {
+      if (fast_ok) SP_LAUNCH(SM_BF16, SM_SIGN_1BIT, true); else SP_LAUNCH(SM_BF16, SM_SIGN_1BIT, false);
+    } else {
+      if (fast_ok) SP_LAUNCH(SM_BF16, SM_SIGN_INT8, true); else SP_LAUNCH(SM_BF16, SM_SIGN_INT8, false);
+    }
+  } else {
+    if (fmt == SM_SIGN_1BIT) {
+      if (fast_ok) SP_LAUNCH(SM_F32, SM_SIGN_1BIT, true); else SP_LAUNCH(SM_F32, SM_SIGN_1BIT, false);
+    } else {
+      if (fast_ok) SP_LAUNCH(SM_F32, SM_SIGN_INT8, true); else SP_LAUNCH(SM_F32, SM_SIGN_INT8, false);
+    }
+  }
+#undef SP_LAUNCH
+  SM_HIP(ctx, hipGetLastError());
+  return SM_OK;
+}
+
+int sm_launch_vote(signmuon_ctx* ctx, const sm_vote_args& v) {
+  const long long n = v.n;
+  const bool want_bits = v.voted && v.vfmt == SM_VOTE_BITS;
+  const bool want_expand = v.counts || v.w || (v.voted && v.vfmt != SM_VOTE_BITS);
+  if (want_bits) {
+    sm_launch_scope sc(ctx, SM_K_VOTE);
+    if (v.fmt == SM_SIGN_1BIT) {
+      const long long words = (n + 63) / 64;
+      const dim3 grid((unsigned)((words + TPB - 1) / TPB));
+      const unsigned long long* sp = reinterpret_cast<const unsigned long long*>(v.signs);
+      unsigned long long* vp = reinterpret_cast<unsigned long long*>(v.voted);
+      if (v.M < 8)
+        hipLaunchKernelGGL(sm_vote_bits_kernel<3>, grid, dim3(TPB), 0, ctx->stream, sp, v.M, words, v.stride_bytes / 8, n, vp);
+      else if (v.M < 32)
+        hipLaunchKernelGGL(sm_vote_bits_kernel<5>, grid, dim3(TPB), 0, ctx->stream, sp, v.M, words, v.stride_bytes / 8, n, vp);
+      else if (v.M < 256)
+        hipLaunchKernelGGL(sm_vote_bits_kernel<8>, grid, dim3(TPB), 0, ctx->stream, sp, v.M, words, v.stride_bytes / 8, n, vp);
+      else
+        hipLaunchKernelGGL(sm_vote_bits_generic_kernel, dim3((unsigned)((words * 8 + TPB - 1) / TPB)), dim3(TPB), 0,
+                           ctx->stream, reinterpret_cast<const unsigned char*>(v.signs), v.M, n, v.stride_bytes,
+                           reinterpret_cast<unsigned char*>(v.voted), words * 8);
+    } else {
+      const long long bytes_out = 8 * ((n + 63) / 64);
+      hipLaunchKernelGGL(sm_vote_int8_bits_kernel, dim3((unsigned)((bytes_out + TPB - 1) / TPB)), dim3(TPB), 0,
+                         ctx->stream, reinterpret_cast<const signed char*>(v.signs), v.M, n, v.stride_bytes,
+                         reinterpret_cast<unsigned char*>(v.voted), bytes_out);
+    }
+    SM_HIP(ctx, hipGetLastError());
+  }
+  if (want_expand) {
+    vote_x_args a;
+    a.signs = v.signs;
+    a.n = n;
+    a.stride_bytes = v.stride_bytes;
+    a.voted = (v.voted && v.vfmt != SM_VOTE_BITS) ? v.voted : nullptr;
+    a.counts = v.counts;
+    a.w = v.w;
+    a.lr = v.lr_scaled;
+    a.M = v.M;
+    a.vfmt = v.vfmt;
+    a.cols = v.cols;
+    a.ld = v.ld;
+    const long long threads = (n + 3) / 4;
+    sm_launch_scope sc(ctx, SM_K_VOTE);
+    if (v.fmt == SM_SIGN_1BIT)
+      hipLaunchKernelGGL(sm_vote_expand_kernel<SM_SIGN_1BIT>, dim3((unsigned)((threads + TPB - 1) / TPB)), dim3(TPB), 0,
+                         ctx->stream, a);
+    else
+      hipLaunchKernelGGL(sm_vote_expand_kernel<SM_SIGN_INT8>, dim3((unsigned)((threads + TPB - 1) / TPB)), dim3(TPB), 0,
+                         ctx->stream, a);
+    SM_HIP(ctx, hipGetLastError());
+  }
+  return SM_OK;
+}
+
+int sm_launch_update(signmuon_ctx* ctx, float* w, const bf16_t* d, int rows, int cols, int ld, float step) {
+  const long long threads = ((long long)rows * cols + 3) / 4;
+  sm_launch_scope sc(ctx, SM_K_UPDATE);
+  hipLaunchKernelGGL(sm_update_kernel, dim3((unsigned)((threads + TPB - 1) / TPB)), dim3(TPB), 0, ctx->stream, w, d,
+                     rows, cols, ld, step);
+  SM_HIP(ctx, hipGetLastError());
+  return SM_OK;
+}

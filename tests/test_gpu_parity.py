@@ -1,0 +1,339 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle on the same seeded inputs.
+
+Bars: bit-exact for momentum (float32, stated rounding order), sign packing,
+vote, counts and the fused update; PolarNS within 2e-2 relative Frobenius error
+of the float32 oracle with >= 99.9 % sign agreement on entries with
+|x| > 1e-3 * max|x|.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import signmuon_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+NS_REL_TOL = 2e-2
+SIGN_AGREE = 0.999
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2605_16311_amd as pkg
+    return pkg
+
+
+@pytest.fixture(scope="module")
+def ctx(P):
+    c = P.Context()
+    yield c
+    torch.cuda.synchronize()
+    c.close()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def bf16_dev(a_f32):
+    return dev(np.asarray(a_f32, np.float32)).bfloat16()
+
+
+def bf16_host(t):
+    return t.float().cpu().numpy()
+
+
+def ns_check(got, ref, what=""):
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    rel = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
+    big = np.abs(ref) > 1e-3 * np.max(np.abs(ref))
+    agree = np.mean((got[big] >= 0) == (ref[big] >= 0)) if big.any() else 1.0
+    assert rel <= NS_REL_TOL, f"{what}: rel Frobenius {rel:.3e}"
+    assert agree >= SIGN_AGREE, f"{what}: sign agreement {agree:.5f}"
+    return rel, agree
+
+
+# ------------------------------------------------------------------ a1
+@pytest.mark.parametrize("M,r,c,wd", [(4, 256, 256, 0.0), (3, 37, 53, 0.0), (2, 64, 576, 0.1),
+                                      (5, 129, 100, 0.05), (1, 1, 1, 0.0), (2, 1000, 2048, 0.0)])
+def test_momentum_bit_exact(P, ctx, M, r, c, wd):
+    g = wl.worker_grads("single256", 0, r, c, M=M)
+    m0 = wl.normal((M, r, c), stream=21)
+    w = wl.weights(r, c)
+    ref = O.momentum_update(m0, g, w, 0.9, wd, dtype=np.float32)
+    mom, x = dev(m0), torch.empty((M, r, c), dtype=torch.bfloat16, device="cuda")
+    ss = torch.empty(M, dtype=torch.float32, device="cuda")
+    P.signmuon_momentum(ctx, mom, dev(g), dev(w) if wd else None, 0.9, wd, x_bf16=x, sumsq=ss)
+    got = mom.cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+    assert np.array_equal(bf16_host(x), wl.from_bf16_bits(wl.to_bf16_bits(ref)))
+    ss_ref = np.sum(ref.astype(np.float64) ** 2, axis=(1, 2))
+    assert np.allclose(ss.cpu().numpy(), ss_ref, rtol=1e-5)
+    # second step from the new state, no side outputs
+    ref2 = O.momentum_update(ref, g, w, 0.9, wd, dtype=np.float32)
+    P.signmuon_momentum(ctx, mom, dev(g), dev(w) if wd else None, 0.9, wd)
+    assert np.array_equal(mom.cpu().numpy().view(np.uint32), ref2.view(np.uint32))
+
+
+# ------------------------------------------------------------------ a5
+@pytest.mark.parametrize("n", [1, 7, 8, 63, 64, 65, 1000, 4096, 65536 + 13, 300001])
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_sign_pack_bit_exact(P, ctx, n, dt):
+    batch = 3
+    x = wl.normal((batch, n), stream=22, block=n)
+    sv = wl.special_values_f32()
+    x[0, : min(n, sv.size)] = sv[: min(n, sv.size)]
+    x[1, ::3] = 0.0
+    x[2, 1::5] = -0.0
+    if dt == "bf16":
+        xb = wl.from_bf16_bits(wl.to_bf16_bits(x))
+        u = dev(wl.to_bf16_bits(x).view(np.int16)).view(torch.bfloat16)
+    else:
+        xb, u = x, dev(x)
+    stride = O.packed_stride_bytes(n)
+    out = torch.full((batch, stride + 8), 0xAA, dtype=torch.uint8, device="cuda")
+    P.signmuon_sign_pack(ctx, u, "1bit", out)
+    got = out.cpu().numpy()
+    for b in range(batch):
+        assert np.array_equal(got[b, :stride], O.pack_bits(O.sign_entries(xb[b]))), (n, dt, b)
+        assert np.all(got[b, stride:] == 0xAA)          # nothing written past the row
+    o8 = torch.full((batch, n + 5), 7, dtype=torch.int8, device="cuda")
+    P.signmuon_sign_pack(ctx, u, "int8", o8)
+    g8 = o8.cpu().numpy()
+    for b in range(batch):
+        assert np.array_equal(g8[b, :n], O.signs_pm1(xb[b]))
+        assert np.all(g8[b, n:] == 7)
+
+
+def test_sign_pack_empty_and_errors(P, ctx):
+    u = torch.empty((2, 0), dtype=torch.float32, device="cuda")
+    out = torch.zeros((2, 8), dtype=torch.uint8, device="cuda")
+    P.signmuon_sign_pack(ctx, u, "1bit", out)
+    u = torch.zeros((1, 100), dtype=torch.float32, device="cuda")
+    with pytest.raises(P.SignMuonError):
+        P.signmuon_sign_pack(ctx, u, "1bit", torch.zeros((1, 8), dtype=torch.uint8, device="cuda"))
+    with pytest.raises(P.SignMuonError):
+        P.signmuon_sign_pack(ctx, u, "int8", torch.zeros((1, 50), dtype=torch.int8, device="cuda"))
+
+
+# ------------------------------------------------------------------ a6 (+ a8)
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 8, 16, 33, 300])
+@pytest.mark.parametrize("n", [1, 5, 64, 100, 4099, 70001])
+def test_vote_bit_exact(P, ctx, M, n):
+    rng = wl.rng_for(23, block=M, worker=n)
+    S = rng.choice(np.array([-1, 1], np.int8), size=(M, n), p=[0.45, 0.55])
+    S[:, : min(n, 4)] = 1
+    if M % 2 == 0 and n > 8:
+        S[: M // 2, 5] = 1
+        S[M // 2:, 5] = -1                                    # a forced tie
+    packed = np.stack([O.pack_bits((S[p] > 0).astype(np.uint8)) for p in range(M)])
+    stride = packed.shape[1]
+    vote_ref, tot_ref = O.majority_vote_int8(S)
+    vote1_ref, c_ref = O.majority_vote_bits(packed, M, n)
+    assert np.array_equal(vote_ref, vote1_ref)
+    w0 = wl.normal((n,), stream=24, block=n)
+    lr = 0.01
+    w_ref = O.apply_update(w0.reshape(1, n), vote_ref.reshape(1, n), lr, dtype=np.float32).reshape(n)
+    for fmt, signs, counts_ref, sb in (("1bit", packed, c_ref, stride), ("int8", S, tot_ref, n)):
+        d_signs = dev(signs)
+        # voted bits
+        vb = torch.full((stride + 8,), 0x55, dtype=torch.uint8, device="cuda")
+        P.signmuon_majority_vote(ctx, d_signs, fmt, M, n, sb, voted=vb, vfmt="bits")
+        g = vb.cpu().numpy()
+        assert np.array_equal(g[:stride], O.pack_bits((vote_ref > 0).astype(np.uint8))), (fmt, M, n)
+        assert np.all(g[stride:] == 0x55)
+        # expanded formats + counts + fused update, one call each
+        cnt = torch.full((n + 4,), -7, dtype=torch.int32, device="cuda")
+        w = dev(np.concatenate([w0, np.full(4, 3.0, np.float32)]))
+        v8 = torch.full((n + 4,), 9, dtype=torch.int8, device="cuda")
+        P.signmuon_majority_vote(ctx, d_signs, fmt, M, n, sb, voted=v8, vfmt="int8", counts=cnt, w=w, lr_scaled=lr)
+        assert np.array_equal(v8.cpu().numpy()[:n], vote_ref) and np.all(v8.cpu().numpy()[n:] == 9)
+        assert np.array_equal(cnt.cpu().numpy()[:n], counts_ref) and np.all(cnt.cpu().numpy()[n:] == -7)
+        gw = w.cpu().numpy()
+        assert np.array_equal(gw[:n].view(np.uint32), w_ref.view(np.uint32)) and np.all(gw[n:] == 3.0)
+        vb16 = torch.zeros((n + 4,), dtype=torch.bfloat16, device="cuda")
+        P.signmuon_majority_vote(ctx, d_signs, fmt, M, n, sb, voted=vb16, vfmt="bf16")
+        assert np.array_equal(bf16_host(vb16)[:n], vote_ref.astype(np.float32)) and np.all(bf16_host(vb16)[n:] == 0)
+        vf = torch.zeros((n + 4,), dtype=torch.float32, device="cuda")
+        P.signmuon_majority_vote(ctx, d_signs, fmt, M, n, sb, voted=vf, vfmt="f32")
+        assert np.array_equal(vf.cpu().numpy()[:n], vote_ref.astype(np.float32)) and np.all(vf.cpu().numpy()[n:] == 0)
+
+
+def test_vote_ignores_garbage_tail_bits_and_dropped_worker(P, ctx):
+    M, n = 5, 70
+    rng = wl.rng_for(25)
+    S = rng.choice(np.array([-1, 1], np.int8), size=(M, n))
+    packed = np.stack([O.pack_bits((S[p] > 0).astype(np.uint8)) for p in range(M)])
+    ref, _ = O.majority_vote_int8(S)
+    dirty = packed.copy()
+    dirty[:, n // 8] |= np.uint8(0xFF << (n % 8) & 0xFF)      # set padding bits in every worker
+    dirty[:, n // 8 + 1:] = 0xFF
+    vb = torch.zeros((16,), dtype=torch.uint8, device="cuda")
+    P.signmuon_majority_vote(ctx, dev(dirty), "1bit", M, n, 16, voted=vb, vfmt="bits")
+    assert np.array_equal(vb.cpu().numpy(), O.pack_bits((ref > 0).astype(np.uint8)))
+    # a dropped worker: vote over the first M-1 rows only
+    ref4, _ = O.majority_vote_int8(S[:4])
+    P.signmuon_majority_vote(ctx, dev(packed), "1bit", 4, n, 16, voted=vb, vfmt="bits")
+    assert np.array_equal(vb.cpu().numpy(), O.pack_bits((ref4 > 0).astype(np.uint8)))
+
+
+# ------------------------------------------------------------------ a2-a4
+NS_CASES = [
+    # (batch, rows, cols, steps, scale, coeffs)
+    (4, 256, 256, 5, "fro", O.PAPER_COEFFS),
+    (2, 64, 576, 5, "fro", O.PAPER_COEFFS),
+    (2, 576, 64, 5, "fro", O.PAPER_COEFFS),
+    (3, 128, 320, 3, "fro", O.PAPER_COEFFS),
+    (2, 200, 136, 5, "fro", O.PAPER_COEFFS),        # padding in both dimensions, tall
+    (2, 100, 333, 4, "fro", O.PAPER_COEFFS),        # padding, wide, odd sizes
+    (1, 512, 1152, 5, "fro", O.PAPER_COEFFS),
+    (2, 256, 256, 1, "fro", O.PAPER_COEFFS),
+    (2, 192, 448, 0, "fro", O.PAPER_COEFFS),        # K = 0: only the scaling
+    (2, 256, 384, 5, "spectral", O.PAPER_COEFFS),
+    (2, 384, 256, 5, "spectral", O.PAPER_COEFFS),
+    (2, 128, 128, 4, "none", O.PAPER_COEFFS),
+    (2, 192, 320, 3, "fro", (2.0, -1.5, 0.5)),      # quintic polynomial
+]
+
+
+@pytest.mark.parametrize("batch,r,c,steps,scale,coeffs", NS_CASES)
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_polar_ns_against_fp32_oracle(P, ctx, batch, r, c, steps, scale, coeffs, dt):
+    x = wl.normal((batch, r, c), stream=26, block=r, worker=c)
+    if scale == "none":
+        x = x / (1.05 * np.linalg.norm(x, ord=2, axis=(1, 2), keepdims=True)).astype(np.float32)
+    v0 = wl.start_vectors(batch, c, block=r)
+    if dt == "bf16":
+        xin = wl.from_bf16_bits(wl.to_bf16_bits(x))
+        xd = dev(wl.to_bf16_bits(x).view(np.int16)).view(torch.bfloat16)
+    else:
+        xin, xd = x, dev(x)
+    P.signmuon_polar_ns(ctx, xd, steps, coeffs=coeffs, scale=scale, power_iters=2, eps=1e-12,
+                        v0=dev(v0) if scale == "spectral" else None)
+    got = xd.float().cpu().numpy()
+    for b in range(batch):
+        ref = O.polar_ns(xin[b], steps, coeffs, scale, 2, 1e-12, v0[b], dtype=np.float32)
+        ns_check(got[b], ref, f"{(batch, r, c, steps, scale, dt)} item {b}")
+
+
+def test_polar_ns_zero_matrix_and_errors(P, ctx):
+    x = torch.zeros((2, 64, 128), dtype=torch.float32, device="cuda")
+    P.signmuon_polar_ns(ctx, x, 5)
+    assert torch.all(x == 0) and not torch.isnan(x).any()
+    with pytest.raises(P.SignMuonError):
+        P.signmuon_polar_ns(ctx, x, 5, scale="spectral")          # no v0
+    with pytest.raises(P.SignMuonError):
+        P.signmuon_polar_ns(ctx, x, -1)
+
+
+# ------------------------------------------------------------------ whole step
+def run_step_case(P, ctx, shapes, M, *, sign_fmt, Kp, K=5, scale="fro", wd=0.0, rsqrt=False, stream=31,
+                  grads=None, check_ns_blocks=None):
+    n = len(shapes)
+    lr, beta = 1e-3, 0.9
+    W0 = [wl.weights(r, c, block=i, stream=stream) for i, (r, c) in enumerate(shapes)]
+    G = grads or [wl.normal((M, r, c), stream=stream, block=i, worker=7) for i, (r, c) in enumerate(shapes)]
+    M0 = [0.1 * wl.normal((M, r, c), stream=stream, block=i, worker=8) for i, (r, c) in enumerate(shapes)]
+    V0 = [wl.start_vectors(M, c, block=i, stream=stream) for i, (r, c) in enumerate(shapes)]
+    w = [dev(a) for a in W0]
+    mom = [dev(a) for a in M0]
+    grad = [dev(a) for a in G]
+    v0 = [dev(a) for a in V0] if scale == "spectral" else None
+    d = [r * c for r, c in shapes]
+    sstride = [O.packed_stride_bytes(x) if sign_fmt == "1bit" else x for x in d]
+    signs = [torch.zeros((M, s), dtype=torch.uint8, device="cuda") for s in sstride]
+    counts = [torch.zeros((x,), dtype=torch.int32, device="cuda") for x in d]
+    u_out = [torch.zeros((M, r, c), dtype=torch.bfloat16, device="cuda") for r, c in shapes]
+    d_out = [torch.zeros((r, c), dtype=torch.bfloat16, device="cuda") for r, c in shapes]
+    plan = P.StepPlan(w, mom, grad, beta=beta, lr=lr, ns_steps=K, weight_decay=wd, scale=scale, v0=v0,
+                      sign_fmt=sign_fmt, local_polar_steps=Kp, update_rsqrt_mn=rsqrt,
+                      signs_out=signs, counts_out=counts, u_out=u_out, d_out=d_out)
+    P.signmuon_step(ctx, plan)
+    torch.cuda.synchronize()
+    for i, (r, c) in enumerate(shapes):
+        # a1: momentum bit-exact
+        m_ref = O.momentum_update(M0[i], G[i], W0[i], beta, wd, dtype=np.float32)
+        assert np.array_equal(mom[i].cpu().numpy().view(np.uint32), m_ref.view(np.uint32)), f"momentum block {i}"
+        U = bf16_host(u_out[i])
+        # a2-a4: U against the float32 oracle (on selected blocks: it is the slow part)
+        if check_ns_blocks is None or i in check_ns_blocks:
+            for p in range(M):
+                ref = O.polar_ns(m_ref[p], K, O.PAPER_COEFFS, scale, 2, 1e-12, V0[i][p], dtype=np.float32)
+                ns_check(U[p], ref, f"U block {i} worker {p}")
+        # a5: the oracle's packing of the GPU's own U, bit-exact
+        if sign_fmt == "1bit":
+            s_ref = np.stack([O.pack_bits(O.sign_entries(U[p])) for p in range(M)])
+            vote_ref, c_ref = O.majority_vote_bits(s_ref, M, d[i])
+        else:
+            s_ref = np.stack([O.signs_pm1(U[p]).reshape(-1) for p in range(M)]).view(np.uint8)
+            vote_ref, c_ref = O.majority_vote_int8(s_ref.view(np.int8))
+        assert np.array_equal(signs[i].cpu().numpy(), s_ref), f"signs block {i}"
+        # a6: vote / counts of those signs, bit-exact
+        assert np.array_equal(counts[i].cpu().numpy(), c_ref), f"counts block {i}"
+        S_bar = vote_ref.reshape(r, c)
+        D = bf16_host(d_out[i])
+        if Kp == 0:
+            assert np.array_equal(D, S_bar.astype(np.float32)), f"vote block {i}"
+        elif check_ns_blocks is None or i in check_ns_blocks:
+            # a7: local polar of the voted matrix against the float32 oracle
+            ref = O.local_polar(S_bar, Kp, O.PAPER_COEFFS, scale, 2, 1e-12, V0[i][0], dtype=np.float32)
+            ns_check(D, ref, f"D block {i}")
+        # a8: W - step * D with the GPU's own D, bit-exact
+        w_ref = O.apply_update(W0[i], D, lr, rsqrt, dtype=np.float32)
+        assert np.array_equal(w[i].cpu().numpy().view(np.uint32), w_ref.view(np.uint32)), f"W block {i}"
+    return plan
+
+
+def test_step_single256(P, ctx):
+    """256x256, M=4, N(0,1) gradients from zero momentum, 5 NS steps, 1-bit, no local polar."""
+    cfg = wl.WORKLOADS["single256"]
+    shapes, M = cfg["shapes"], cfg["M"]
+    G = [wl.worker_grads("single256", 0, 256, 256)]
+    run_step_case(P, ctx, shapes, M, sign_fmt="1bit", Kp=0, grads=G)
+
+
+@pytest.mark.parametrize("sign_fmt", ["1bit", "int8"])
+@pytest.mark.parametrize("Kp", [0, 3])
+def test_step_mixed_set(P, ctx, sign_fmt, Kp):
+    shapes = [(64, 192), (192, 64), (64, 192), (128, 128), (100, 72), (64, 192)]
+    run_step_case(P, ctx, shapes, 3, sign_fmt=sign_fmt, Kp=Kp, wd=0.1, rsqrt=(Kp > 0))
+
+
+def test_step_spectral(P, ctx):
+    run_step_case(P, ctx, [(128, 256), (256, 128)], 2, sign_fmt="1bit", Kp=2, scale="spectral")
+
+
+def test_step_signsgd_limit_and_zero_gradients(P, ctx):
+    # K = 0, beta = 0, M = 1: W - lr * sign(G)
+    r, c = 48, 80
+    G = wl.normal((1, r, c), stream=32)
+    W0 = wl.weights(r, c, stream=32)
+    w, mom, grad = [dev(W0)], [torch.zeros((1, r, c), device="cuda")], [dev(G)]
+    plan = P.StepPlan(w, mom, grad, beta=0.0, lr=0.25, ns_steps=0)
+    P.signmuon_step(ctx, plan)
+    ref = O.signmuon_step(W0, np.zeros_like(G), G, beta=0.0, lr=0.25, ns_steps=0, dtype=np.float32)
+    assert np.array_equal(w[0].cpu().numpy(), ref["W"])
+    # all-zero gradients from zero state: every sign bit is 1, W decreases by lr
+    w = [torch.ones((r, c), device="cuda")]
+    z = [torch.zeros((3, r, c), device="cuda")]
+    plan = P.StepPlan(w, [z[0].clone()], z, beta=0.9, lr=0.5, ns_steps=5)
+    P.signmuon_step(ctx, plan)
+    assert torch.all(w[0] == 0.5)
+
+
+def test_step_is_deterministic_and_repeatable(P, ctx):
+    shapes, M = [(128, 256), (256, 128)], 4
+    outs = []
+    for _ in range(2):
+        W0 = [wl.weights(r, c, block=i, stream=33) for i, (r, c) in enumerate(shapes)]
+        w = [dev(a) for a in W0]
+        mom = [torch.zeros((M, r, c), device="cuda") for r, c in shapes]
+        grad = [dev(wl.normal((M, r, c), stream=33, block=i)) for i, (r, c) in enumerate(shapes)]
+        plan = P.StepPlan(w, mom, grad, beta=0.9, lr=1e-2, ns_steps=5, local_polar_steps=2)
+        for _ in range(3):
+            P.signmuon_step(ctx, plan)
+        outs.append([t.cpu().numpy() for t in w + mom])
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
