@@ -1,0 +1,249 @@
+#!/usr/bin/env python3
+"""Benchmark of the Sign-Muon optimizer hot path on one MI355X.
+
+A step is one signmuon_step call: for every weight block of the workload and all
+M simulated workers, momentum -> Newton-Schulz -> sign pack -> majority vote ->
+(local polar) -> update.  Inputs are synthetic, seeded, resident in HBM before
+the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+
+
+def ns_flops(shapes, batch_per_block, steps):
+    """Nominal Newton-Schulz work: 4 s^2 l per step and matrix (Gram 2 s^2 l + apply 2 s^2 l)."""
+    gram = apply_ = 0.0
+    for r, c in shapes:
+        s, l = min(r, c), max(r, c)
+        gram += 2.0 * s * s * l * batch_per_block * steps
+        apply_ += 2.0 * s * s * l * batch_per_block * steps
+    return gram, apply_
+
+
+def make_inputs(name, torch, device):
+    import workloads as wl
+    cfg = wl.WORKLOADS[name]
+    M = cfg["M"]
+    gen = torch.Generator(device=device)
+    gen.manual_seed(wl.BASE_SEED * 1000 + cfg["stream"])
+    w, mom, grad = [], [], []
+    for r, c in cfg["shapes"]:
+        w.append(torch.randn((r, c), generator=gen, device=device) * 0.02)
+        mom.append(torch.zeros((M, r, c), device=device))
+        kind = cfg["grad"]
+        if kind == "normal":
+            g = torch.randn((M, r, c), generator=gen, device=device) * cfg["grad_std"]
+        elif kind == "lowrank":
+            k = cfg["rank"]
+            A = torch.randn((r, k), generator=gen, device=device)
+            B = torch.randn((c, k), generator=gen, device=device)
+            g = (A @ B.T / math.sqrt(k))[None] + torch.randn((M, r, c), generator=gen, device=device)
+        elif kind == "student_t":
+            nu = cfg["nu"]
+            z = torch.randn((M, r, c), generator=gen, device=device)
+            chi = torch.zeros((M, r, c), device=device)
+            for _ in range(nu):
+                chi += torch.randn((M, r, c), generator=gen, device=device) ** 2
+            g = z / torch.sqrt(chi / nu)
+            del z, chi
+        else:
+            raise ValueError(kind)
+        grad.append(g.contiguous())
+    return cfg, w, mom, grad
+
+
+def run_workload(name, steps, warmup, torch, P, B):
+    device = torch.device("cuda:0")
+    cfg, w, mom, grad = make_inputs(name, torch, device)
+    shapes, M = cfg["shapes"], cfg["M"]
+    K, Kp = cfg["ns_steps"], cfg["local_polar_steps"]
+    ctx = P.Context()
+    plan = P.StepPlan(w, mom, grad, beta=0.9, lr=1e-3, ns_steps=K, sign_fmt=cfg["sign_fmt"],
+                      local_polar_steps=Kp, scale="fro")
+    for _ in range(warmup):
+        P.signmuon_step(ctx, plan)
+    torch.cuda.synchronize()
+    # timed region: only the two GEMM classes carry event taps here (a few dozen launches per step)
+    ctx.profile_reset()
+    ctx.profile_enable((1 << B.SM_K_NS_GRAM) | (1 << B.SM_K_NS_APPLY))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        P.signmuon_step(ctx, plan)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    elapsed = t1 - t0
+    n_gram, ms_gram = ctx.profile_read(B.SM_K_NS_GRAM)
+    n_apply, ms_apply = ctx.profile_read(B.SM_K_NS_APPLY)
+    # second, untimed pass with taps on every kernel class: per-class breakdown
+    ctx.profile_reset()
+    ctx.profile_enable((1 << B.SM_K_COUNT) - 1)
+    for _ in range(steps):
+        P.signmuon_step(ctx, plan)
+    torch.cuda.synchronize()
+    per_class = {}
+    for k in range(B.SM_K_COUNT):
+        n, ms = ctx.profile_read(k)
+        per_class[P.kernel_name(k)] = {"launches_per_step": n / steps, "ms_per_step": ms / steps}
+    ctx.profile_enable(0)
+    ws = ctx.workspace_bytes
+    ctx.close()
+
+    d_total = sum(r * c for r, c in shapes)
+    g1, a1 = ns_flops(shapes, M, K)
+    g2, a2 = ns_flops(shapes, 1, Kp)
+    gram_flop, apply_flop = g1 + g2, a1 + a2
+    one_bit = cfg["sign_fmt"] == "1bit"
+    pack_bytes = d_total * M * (2 + (0.125 if one_bit else 1.0))
+    if Kp:
+        vote_bytes = d_total * ((M / 8 if one_bit else M) + 2)          # writes the +-1 bf16 matrix
+    else:
+        vote_bytes = d_total * ((M / 8 if one_bit else M) + 8)          # fused W read + write
+    mom_bytes = d_total * M * 14.0
+    ms_pack = per_class[P.kernel_name(B.SM_K_SIGN_PACK)]["ms_per_step"]
+    ms_vote = per_class[P.kernel_name(B.SM_K_VOTE)]["ms_per_step"]
+    ms_mom = per_class[P.kernel_name(B.SM_K_MOMENTUM)]["ms_per_step"]
+    res = {
+        "workload": name, "M": M, "n_blocks": len(shapes), "entries": d_total,
+        "steps_per_s": steps / elapsed, "ms_per_step": 1e3 * elapsed / steps,
+        "ns_tflops": (gram_flop + apply_flop) * steps / ((ms_gram + ms_apply) * 1e-3) / 1e12 if ms_gram + ms_apply else None,
+        "ns_gram": {"launches": n_gram, "avg_ms": ms_gram / max(n_gram, 1),
+                    "tflops": gram_flop * steps / (ms_gram * 1e-3) / 1e12 if ms_gram else None},
+        "ns_apply": {"launches": n_apply, "avg_ms": ms_apply / max(n_apply, 1),
+                     "tflops": apply_flop * steps / (ms_apply * 1e-3) / 1e12 if ms_apply else None,
+                     "flop_per_launch": apply_flop * steps / max(n_apply, 1)},
+        "sign_vote_gbs": (pack_bytes + vote_bytes) / ((ms_pack + ms_vote) * 1e-3) / 1e9 if ms_pack + ms_vote else None,
+        "momentum_gbs": mom_bytes / (ms_mom * 1e-3) / 1e9 if ms_mom else None,
+        "per_class": per_class, "workspace_GB": ws / 1e9,
+    }
+    del w, mom, grad, plan
+    torch.cuda.empty_cache()
+    return res
+
+
+def cpu_baseline(name, budget_s=25.0):
+    """Times the oracle (float32 variant, as it stands) on a bounded sample of the workload."""
+    import numpy as np
+    import workloads as wl
+    from oracle import signmuon_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    cfg = wl.WORKLOADS[name]
+    shapes, M = cfg["shapes"], cfg["M"]
+    # distinct shapes with multiplicity; time whole-step work of one block per distinct shape
+    distinct = {}
+    for s in shapes:
+        distinct[s] = distinct.get(s, 0) + 1
+    total = 0.0
+    timed_workers = 0
+    sample_desc = []
+    for (r, c), count in distinct.items():
+        # a worker's share of one block is independent of the others: time a few workers, scale to M
+        mw = M
+        per_worker_flop = cfg["ns_steps"] * 4.0 * min(r, c) ** 2 * max(r, c)
+        while mw > 1 and mw * per_worker_flop > 1.5e11:
+            mw //= 2
+        G = wl.worker_grads(name, 0, r, c, M=mw)
+        W = wl.weights(r, c)
+        mom = np.zeros_like(G)
+        t0 = time.perf_counter()
+        out = O.signmuon_step(W, mom, G, beta=0.9, lr=1e-3, ns_steps=cfg["ns_steps"],
+                              sign_fmt=cfg["sign_fmt"], local_polar_steps=0, dtype=np.float32)
+        t_workers = time.perf_counter() - t0
+        t_local = 0.0
+        if cfg["local_polar_steps"]:
+            t0 = time.perf_counter()
+            O.local_polar(out["vote"], cfg["local_polar_steps"], dtype=np.float32)
+            t_local = time.perf_counter() - t0
+        total += count * (t_workers * (M / mw) + t_local)
+        timed_workers += mw
+        sample_desc.append(f"{r}x{c}:{mw}of{M}w")
+        if total > 20 * budget_s and False:
+            break
+    return {"value": 1.0 / total, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+            "sample": "float32 oracle, one block per distinct shape (" + ", ".join(sample_desc) +
+                      " workers timed), scaled by block count and M; blocks and workers are independent"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="nanogpt124m")
+    ap.add_argument("--also", default="resnet50", help="second workload reported in the same line ('' to skip)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the M workers are a batch dimension); "
+              "--gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2605_16311_amd as P
+    from paper_2605_16311_amd import binding as B
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    main_res = run_workload(args.workload, args.steps, args.warmup, torch, P, B)
+    also = None
+    if args.also and args.also != args.workload:
+        also = run_workload(args.also, max(args.steps * 5, 50), args.warmup, torch, P, B)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.workload, {}).get("ns_apply_bytes_per_launch")
+        except Exception:
+            traffic = None
+    ach = main_res["ns_apply"]["tflops"]
+    line = {
+        "metric": "Sign-Muon steps/sec; NS TFLOPS (% MFMA peak); sign+vote GB/s (% HBM)",
+        "value": main_res["steps_per_s"], "unit": "steps/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "M": main_res["M"], "blocks": main_res["n_blocks"],
+                   "entries": main_res["entries"], "ns_steps": 5, "scale": "fro"},
+        "roofline": {"kernel": "sm_ns_gemm_nt_kernel (apply)", "bound": "mfma", "achieved": ach,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": (ach / MFMA_BF16_PEAK_TFLOPS) if ach else None, "traffic": traffic,
+                     "avg_launch_ms": main_res["ns_apply"]["avg_ms"],
+                     "flop_per_launch": main_res["ns_apply"]["flop_per_launch"]},
+        "ns": {"tflops": main_res["ns_tflops"], "frac_of_mfma_peak": main_res["ns_tflops"] / MFMA_BF16_PEAK_TFLOPS
+               if main_res["ns_tflops"] else None, "gram": main_res["ns_gram"], "apply": main_res["ns_apply"]},
+        "sign_vote": {"gbs": main_res["sign_vote_gbs"],
+                      "frac_of_hbm_peak": main_res["sign_vote_gbs"] / HBM_PEAK_GBS if main_res["sign_vote_gbs"] else None},
+        "momentum_gbs": main_res["momentum_gbs"],
+        "per_class_ms": {k: round(v["ms_per_step"], 4) for k, v in main_res["per_class"].items()},
+        "workspace_GB": main_res["workspace_GB"],
+    }
+    if also:
+        line["also"] = {k: also[k] for k in ("workload", "M", "n_blocks", "steps_per_s", "ms_per_step", "ns_tflops",
+                                             "sign_vote_gbs", "momentum_gbs")}
+        line["also"]["per_class_ms"] = {k: round(v["ms_per_step"], 4) for k, v in also["per_class"].items()}
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(args.workload)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -164,10 +164,11 @@ typedef struct signmuon_step_args {
 int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* args);
 
 /* ---- timing taps for benchmarks ---------------------------------------- */
-/* When enabled, the library brackets each kernel launch of the listed classes
- * with HIP events on the context's stream; signmuon_profile_read waits for the
- * stream and returns the launch count and summed duration (ms) since the last
- * reset.  Off by default. */
+/* signmuon_profile_enable takes a bit mask of kernel classes (bit SM_K_x set:
+ * every launch of that class is bracketed with HIP events on the context's
+ * stream; 0 = off, the default).  signmuon_profile_read waits for the stream
+ * and returns the launch count and summed duration (ms) of one class since the
+ * last signmuon_profile_reset. */
 #define SM_K_MOMENTUM 0
 #define SM_K_NS_GRAM 1
 #define SM_K_NS_APPLY 2
@@ -176,7 +177,7 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* args);
 #define SM_K_UPDATE 5
 #define SM_K_OTHER 6
 #define SM_K_COUNT 7
-int signmuon_profile_enable(signmuon_ctx* ctx, int on);
+int signmuon_profile_enable(signmuon_ctx* ctx, unsigned class_mask);
 int signmuon_profile_reset(signmuon_ctx* ctx);
 int signmuon_profile_read(signmuon_ctx* ctx, int kernel_class, int64_t* launches, double* total_ms);
 const char* signmuon_kernel_name(int kernel_class);

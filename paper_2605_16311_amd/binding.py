@@ -70,7 +70,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.signmuon_sign_pack.argtypes = [vp, vp, i32, i32, i64, i32, vp, i64]
     lib.signmuon_majority_vote.argtypes = [vp, vp, i32, i32, i64, i64, vp, i32, vp, vp, f32]
     lib.signmuon_step.argtypes = [vp, C.POINTER(StepArgs)]
-    lib.signmuon_profile_enable.argtypes = [vp, i32]
+    lib.signmuon_profile_enable.argtypes = [vp, C.c_uint]
     lib.signmuon_profile_reset.argtypes = [vp]
     lib.signmuon_profile_read.argtypes = [vp, i32, C.POINTER(i64), C.POINTER(C.c_double)]
     lib.signmuon_kernel_name.argtypes = [i32]
@@ -137,8 +137,8 @@ class Context:
         return _lib.signmuon_workspace_bytes(self._h)
 
     # -- timing taps
-    def profile_enable(self, on=True):
-        self._check(_lib.signmuon_profile_enable(self._h, int(on)), "profile_enable")
+    def profile_enable(self, class_mask=(1 << SM_K_COUNT) - 1):
+        self._check(_lib.signmuon_profile_enable(self._h, int(class_mask)), "profile_enable")
 
     def profile_reset(self):
         self._check(_lib.signmuon_profile_reset(self._h), "profile_reset")

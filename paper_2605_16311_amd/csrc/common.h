@@ -35,7 +35,7 @@ struct signmuon_ctx {
   struct ns_plan* plan = nullptr;
 
   // timing taps
-  bool profiling = false;
+  unsigned profiling = 0;  // bit k set: launches of kernel class k are bracketed with events
   std::vector<sm_event_pair> ev_pool;        // every pair ever created
   size_t ev_used = 0;                        // pairs handed out since the last reset
   std::vector<std::pair<int, size_t>> ev_log;  // (kernel class, pool index)

@@ -15,7 +15,7 @@ int sm_hip_fail(signmuon_ctx* ctx, hipError_t e, const char* what) {
 }
 
 sm_launch_scope::sm_launch_scope(signmuon_ctx* c, int k) : ctx(c), klass(k) {
-  if (!ctx->profiling) return;
+  if (!((ctx->profiling >> k) & 1u)) return;
   if (ctx->ev_used == ctx->ev_pool.size()) {
     sm_event_pair p;
     if (hipEventCreate(&p.a) != hipSuccess) return;
@@ -104,9 +104,9 @@ const char* signmuon_last_error(const signmuon_ctx* ctx) { return ctx ? ctx->las
 
 size_t signmuon_workspace_bytes(const signmuon_ctx* ctx) { return ctx ? ctx->arena_bytes : 0; }
 
-int signmuon_profile_enable(signmuon_ctx* ctx, int on) {
+int signmuon_profile_enable(signmuon_ctx* ctx, unsigned class_mask) {
   if (!ctx) return SM_EINVAL;
-  ctx->profiling = on != 0;
+  ctx->profiling = class_mask;
   return SM_OK;
 }
 

@@ -233,7 +233,11 @@ int sm_launch_gemm_nt(signmuon_ctx* ctx, sm_gemm_args& args, int klass) {
         !sm_aligned(P.B, 16) || !sm_aligned(P.C, 16) || P.sA % 8 || P.sB % 8 || P.sC % 8)
       return sm_fail(ctx, SM_EINVAL, "internal: GEMM operand not padded/aligned");
   }
-  int tile = sm_gemm_tile_override;
+  static const int env_tile = [] {
+    const char* e = getenv("SIGNMUON_GEMM_TILE");
+    return e ? atoi(e) : 0;
+  }();
+  int tile = sm_gemm_tile_override ? sm_gemm_tile_override : env_tile;
   if (tile == 0) {
     // large tiles once there is enough work to fill 256 CUs with them
     long long t256 = 0;
