@@ -20,7 +20,7 @@ struct ns_class {
   std::vector<int> members;
   long long mat = 0;       // rp * cp
   // arena offsets in bytes
-  size_t off_x[2] = {0, 0}, off_xt = 0, off_b = 0, off_a = 0, off_sig = 0, off_inv = 0, off_partial = 0;
+  size_t off_x[2] = {0, 0}, off_b = 0, off_a = 0, off_sig = 0, off_inv = 0, off_partial = 0;
   int chunks = 0;          // momentum chunks per worker
 };
 
@@ -101,7 +101,6 @@ int get_plan(signmuon_ctx* ctx, int n, const int* rows, const int* cols, int M, 
     const long long batch = (long long)c.count * M;
     c.off_x[0] = take((size_t)batch * c.mat * 2);
     c.off_x[1] = take((size_t)batch * c.mat * 2);
-    c.off_xt = take((size_t)batch * c.mat * 2);
     c.off_b = take((size_t)batch * c.s * c.s * 2);
     c.off_a = quintic ? take((size_t)batch * c.s * c.s * 2) : 0;
     c.off_sig = take((size_t)batch * 4);
@@ -133,117 +132,104 @@ int get_plan(signmuon_ctx* ctx, int n, const int* rows, const int* cols, int M, 
 // Runs `steps` Newton-Schulz steps on every class, batch = count * mult per class,
 // starting from buffer `cur` (0/1) of each class.  Scales the first step by the
 // per-item inv_sigma when use_scale.  Returns the buffer index holding the result.
+// Per step: one Gram launch and one apply launch for the classes with rows <= cols
+// (Gram over the rows: Bm = a I + b Y Y^T, Y' = Bm Y) and one of each for the others
+// (Gram over the columns: Bm = a I + b Y^T Y, Y' = Y Bm).  Y is read in place in both.
 int run_ns(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coeffs, bool use_scale, int* cur_io) {
   int cur = *cur_io;
   const float a = coeffs[0], b = coeffs[1], c = coeffs[2];
-  const int ncls = (int)pl->classes.size();
   for (int k = 0; k < steps; ++k) {
     const bool sc = use_scale && k == 0;
-    // transposed copies: tall classes need Y^T (K-contiguous rows) for the Gram
-    for (auto& cl : pl->classes) {
-      if (cl.wide) continue;
-      int rc = sm_launch_transpose(ctx, at<bf16_t>(ctx, cl.off_x[cur]), cl.rp, cl.cp, cl.cp, cl.mat,
-                                   at<bf16_t>(ctx, cl.off_xt), cl.rp, cl.mat, cl.count * mult);
-      if (rc != SM_OK) return rc;
-    }
-    // Gram: Bm = a I + b s^2 G (+ c (s^2 G)^2), G = Y Y^T over the short side
-    for (int c0 = 0; c0 < ncls; c0 += SM_GEMM_MAX_PROB) {
-      const int g = std::min(ncls - c0, SM_GEMM_MAX_PROB);
-      sm_gemm_args ga;
-      ga.n_prob = g;
-      ga.scale_pow = sc ? 2 : 0;
-      ga.alpha = (c != 0.f) ? 1.f : b;
-      ga.gamma = 0.f;
-      ga.diag = (c != 0.f) ? 0.f : a;
-      ga.pad_ = 0;
-      for (int i = 0; i < g; ++i) {
-        ns_class& cl = pl->classes[c0 + i];
-        sm_gemm_prob& P = ga.p[i];
-        const bf16_t* y = cl.wide ? at<bf16_t>(ctx, cl.off_x[cur]) : at<bf16_t>(ctx, cl.off_xt);
-        P.A = y;
-        P.B = y;
-        P.C = (c != 0.f) ? at<bf16_t>(ctx, cl.off_a) : at<bf16_t>(ctx, cl.off_b);
-        P.R = nullptr;
-        P.scale = sc ? at<float>(ctx, cl.off_inv) : nullptr;
-        P.sA = P.sB = cl.mat;
-        P.sC = (long long)cl.s * cl.s;
-        P.M = P.N = cl.s;
-        P.K = cl.l;
-        P.lda = P.ldb = cl.l;
-        P.ldc = cl.s;
-        P.batch = cl.count * mult;
-        P.pad_ = 0;
-      }
-      int rc = sm_launch_gemm_nt(ctx, ga, SM_K_NS_GRAM);
-      if (rc != SM_OK) return rc;
-      if (c != 0.f) {  // Bm = c A A^T + b A + a I   (A symmetric)
-        ga.scale_pow = 0;
-        ga.alpha = c;
-        ga.gamma = b;
-        ga.diag = a;
-        for (int i = 0; i < g; ++i) {
-          ns_class& cl = pl->classes[c0 + i];
-          sm_gemm_prob& P = ga.p[i];
-          P.A = P.B = P.R = at<bf16_t>(ctx, cl.off_a);
-          P.C = at<bf16_t>(ctx, cl.off_b);
-          P.scale = nullptr;
-          P.sA = P.sB = P.sC = (long long)cl.s * cl.s;
-          P.M = P.N = P.K = cl.s;
-          P.lda = P.ldb = P.ldc = cl.s;
+    for (int phase = 0; phase < 2; ++phase) {      // 0: Gram, 1: apply
+      for (int wide = 1; wide >= 0; --wide) {
+        std::vector<ns_class*> group;
+        for (auto& cl : pl->classes)
+          if ((int)cl.wide == wide) group.push_back(&cl);
+        for (size_t c0 = 0; c0 < group.size(); c0 += SM_GEMM_MAX_PROB) {
+          const int g = (int)std::min(group.size() - c0, (size_t)SM_GEMM_MAX_PROB);
+          sm_gemm_args ga;
+          ga.n_prob = g;
+          ga.pad_ = 0;
+          ga.gamma = 0.f;
+          if (phase == 0) {
+            ga.scale_pow = sc ? 2 : 0;
+            ga.alpha = (c != 0.f) ? 1.f : b;
+            ga.diag = (c != 0.f) ? 0.f : a;
+          } else {
+            ga.scale_pow = sc ? 1 : 0;
+            ga.alpha = 1.f;
+            ga.diag = 0.f;
+          }
+          for (int i = 0; i < g; ++i) {
+            ns_class& cl = *group[c0 + i];
+            sm_gemm_prob& P = ga.p[i];
+            bf16_t* y = at<bf16_t>(ctx, cl.off_x[cur]);
+            bf16_t* bm = at<bf16_t>(ctx, cl.off_b);
+            const long long ss = (long long)cl.s * cl.s;
+            P.R = nullptr;
+            P.scale = sc ? at<float>(ctx, cl.off_inv) : nullptr;
+            P.batch = cl.count * mult;
+            P.pad_ = 0;
+            if (phase == 0) {  // C[s][s] from Y: rows of Y (wide, K-contiguous) or columns of Y (tall)
+              P.A = P.B = y;
+              P.C = (c != 0.f) ? at<bf16_t>(ctx, cl.off_a) : bm;
+              P.sA = P.sB = cl.mat;
+              P.sC = ss;
+              P.M = P.N = cl.s;
+              P.K = cl.l;
+              P.lda = P.ldb = cl.cp;
+              P.ldc = cl.s;
+            } else {
+              P.C = at<bf16_t>(ctx, cl.off_x[cur ^ 1]);
+              P.sC = cl.mat;
+              P.M = cl.rp;
+              P.N = cl.cp;
+              P.ldc = cl.cp;
+              P.K = cl.s;
+              if (wide) {  // Y'[rp][cp] = Bm[rp][rp] * Y[rp][cp]: second operand is [K][N]
+                P.A = bm;
+                P.B = y;
+                P.sA = ss;
+                P.sB = cl.mat;
+                P.lda = cl.s;
+                P.ldb = cl.cp;
+              } else {     // Y'[rp][cp] = Y[rp][cp] * Bm[cp][cp]^T, Bm symmetric
+                P.A = y;
+                P.B = bm;
+                P.sA = cl.mat;
+                P.sB = ss;
+                P.lda = cl.cp;
+                P.ldb = cl.s;
+              }
+            }
+          }
+          int rc;
+          if (phase == 0) {
+            rc = sm_launch_gemm_pipe(ctx, ga, SM_K_NS_GRAM, wide ? 0 : 3, true);
+            if (rc != SM_OK) return rc;
+            if (c != 0.f) {  // Bm = c A A^T + b A + a I   (A symmetric)
+              ga.scale_pow = 0;
+              ga.alpha = c;
+              ga.gamma = b;
+              ga.diag = a;
+              for (int i = 0; i < g; ++i) {
+                ns_class& cl = *group[c0 + i];
+                sm_gemm_prob& P = ga.p[i];
+                P.A = P.B = P.R = at<bf16_t>(ctx, cl.off_a);
+                P.C = at<bf16_t>(ctx, cl.off_b);
+                P.scale = nullptr;
+                P.sA = P.sB = P.sC = (long long)cl.s * cl.s;
+                P.M = P.N = P.K = cl.s;
+                P.lda = P.ldb = P.ldc = cl.s;
+              }
+              rc = sm_launch_gemm_pipe(ctx, ga, SM_K_NS_GRAM, 0, true);
+            }
+          } else {
+            rc = sm_launch_gemm_pipe(ctx, ga, SM_K_NS_APPLY, wide ? 2 : 0, false);
+          }
+          if (rc != SM_OK) return rc;
         }
-        rc = sm_launch_gemm_nt(ctx, ga, SM_K_NS_GRAM);
-        if (rc != SM_OK) return rc;
       }
-    }
-    // wide classes need Y^T as the K-contiguous second operand of Bm * Y
-    for (auto& cl : pl->classes) {
-      if (!cl.wide) continue;
-      int rc = sm_launch_transpose(ctx, at<bf16_t>(ctx, cl.off_x[cur]), cl.rp, cl.cp, cl.cp, cl.mat,
-                                   at<bf16_t>(ctx, cl.off_xt), cl.rp, cl.mat, cl.count * mult);
-      if (rc != SM_OK) return rc;
-    }
-    // apply: Y' = s * Bm Y (wide) or s * Y Bm (tall)
-    for (int c0 = 0; c0 < ncls; c0 += SM_GEMM_MAX_PROB) {
-      const int g = std::min(ncls - c0, SM_GEMM_MAX_PROB);
-      sm_gemm_args ga;
-      ga.n_prob = g;
-      ga.scale_pow = sc ? 1 : 0;
-      ga.alpha = 1.f;
-      ga.gamma = 0.f;
-      ga.diag = 0.f;
-      ga.pad_ = 0;
-      for (int i = 0; i < g; ++i) {
-        ns_class& cl = pl->classes[c0 + i];
-        sm_gemm_prob& P = ga.p[i];
-        if (cl.wide) {  // C[rp][cp] = Bm[rp][rp] * (Yt[cp][rp])^T
-          P.A = at<bf16_t>(ctx, cl.off_b);
-          P.B = at<bf16_t>(ctx, cl.off_xt);
-          P.sA = (long long)cl.s * cl.s;
-          P.sB = cl.mat;
-          P.lda = cl.s;
-          P.ldb = cl.rp;
-          P.K = cl.rp;
-        } else {        // C[rp][cp] = Y[rp][cp] * (Bm[cp][cp])^T, Bm symmetric
-          P.A = at<bf16_t>(ctx, cl.off_x[cur]);
-          P.B = at<bf16_t>(ctx, cl.off_b);
-          P.sA = cl.mat;
-          P.sB = (long long)cl.s * cl.s;
-          P.lda = cl.cp;
-          P.ldb = cl.s;
-          P.K = cl.cp;
-        }
-        P.C = at<bf16_t>(ctx, cl.off_x[cur ^ 1]);
-        P.R = nullptr;
-        P.scale = sc ? at<float>(ctx, cl.off_inv) : nullptr;
-        P.sC = cl.mat;
-        P.M = cl.rp;
-        P.N = cl.cp;
-        P.ldc = cl.cp;
-        P.batch = cl.count * mult;
-        P.pad_ = 0;
-      }
-      int rc = sm_launch_gemm_nt(ctx, ga, SM_K_NS_APPLY);
-      if (rc != SM_OK) return rc;
     }
     cur ^= 1;
   }

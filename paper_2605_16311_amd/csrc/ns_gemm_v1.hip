@@ -1,0 +1,335 @@
+// Newton-Schulz GEMMs of Alg. PolarNS on the gfx950 matrix cores: the pipelined kernel.
+//
+//   C = alpha * scale^pow * (opA * opB^T) + gamma * R + diag * I      (bf16 in, fp32 accumulate)
+//
+// opA is an M x K operand and opB an N x K operand; each may be stored K-contiguous
+// ([rows][K], "KC") or MN-contiguous ([K][rows], "MN").  The four steps of the iteration are
+//   Gram,  rows <= cols : A = B = Y           (KC, KC)   symmetric output
+//   Gram,  rows >  cols : A = B = Y           (MN, MN)   symmetric output
+//   apply, rows <= cols : A = Bm, B = Y       (KC, MN)   Y' = Bm Y
+//   apply, rows >  cols : A = Y,  B = Bm      (KC, KC)   Y' = Y Bm   (Bm symmetric)
+// so Y is only ever read in its own row-major layout and no transposed copy exists.
+//
+// Structure.  A workgroup of 8 waves (2 per SIMD) owns a 256 x 256 tile of C; each wave a
+// 128 x 64 sub-tile held as 4 x 2 accumulators of v_mfma_f32_32x32x16_bf16.  K advances in
+// slices of 32.  Slices travel global -> LDS with buffer_load_dwordx4 ... lds (no staging
+// registers) into a ring of four stages: while slice t is multiplied, slice t+1 is already
+// resident (its first fragments are fetched before the barrier, so the matrix pipe does not
+// drain), slice t+2 is landing and slice t+3 is being issued.  One barrier per slice, preceded
+// by a vmcnt wait that leaves only the newest slice in flight.  Each stage is its own
+// __shared__ array so the compiler can tell the LDS reads of one stage from the pending
+// global->LDS writes of another.
+//
+// LDS layouts (16 KiB per operand slice).  The LDS serves a 16-byte read sixteen lanes at a
+// time, one 16-byte bank group per lane, and an 8-byte read thirty-two lanes at a time:
+//   KC: 256 rows of 64 bytes; chunk c of row r sits at slot c ^ ((r >> 2) & 3); fragments are
+//       read with ds_read_b128.
+//   MN: 32 k-rows of 512 bytes; 16-byte chunk c of k-row k sits at slot c ^ (4 (k & 3));
+//       fragments are read with ds_read_b64_tr_b16, which hands lane i of a 16-lane group
+//       column i of the 4 x 16 block whose rows the group's lanes address.
+// The global->LDS load writes its 64 lanes in order, so each lane fetches the chunk that
+// belongs in its slot.
+//
+// Symmetric outputs: only tiles with tile_m <= tile_n are computed; off-diagonal tiles are
+// also stored mirrored.
+#include "common.h"
+
+namespace sm_pipe {
+
+constexpr int BM = 256, BN = 256, BK = 32, NTH = 512;
+constexpr int WM = 128, WN = 64, FM = 4, FN = 2;
+constexpr int OPB = 256 * BK * 2;  // bytes of one operand slice: 16 KiB
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+// Per-lane constants of one operand: where its global->LDS loads read, where its fragments sit.
+template <bool MN>
+struct operand_lane {
+  int voff[2];    // byte offset of this lane's two wave-loads inside the operand (slice offset is scalar)
+  int frag_off;   // KC: LDS byte offset of fragment 0 (ks = 0) for this lane
+  int frag_mn[4]; // MN: LDS byte offset of fragment f (ks = 0, first half) for this lane
+  int ks_off[2];  // offset of k-step 0, 1 inside the slice
+  int kstep;      // scalar byte step per K slice
+
+  // row0: first tile row of the workgroup; wrow: first row of this wave's sub-tile inside the tile
+  __device__ __forceinline__ void init(int lane, int wv, int row0, int rows, int ld, int wrow) {
+    if (!MN) {
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int row = 16 * (2 * wv + q) + (lane >> 2);
+        const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+        voff[q] = (min(row0 + row, rows - 1) * ld + chunk * 8) * 2;
+      }
+      const int fr = lane & 31, fg = lane >> 5, fsw = (fr >> 2) & 3;
+      frag_off = (wrow + fr) * (BK * 2);
+      ks_off[0] = ((0 + fg) ^ fsw) * 16;
+      ks_off[1] = ((2 + fg) ^ fsw) * 16;
+      kstep = BK * 2;
+    } else {
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int k = 2 * (2 * wv + q) + (lane >> 5);
+        const int chunk = (lane & 31) ^ (4 * (k & 3));
+        voff[q] = (k * ld + min(row0 + chunk * 8, rows - 8)) * 2;
+      }
+      // transposed read: 16-lane group g16, lane i in it; the group covers columns 16 (g16 & 1) ..+15
+      // and k rows 8 (g16 >> 1) + 4 h + (i >> 2), h = 0, 1
+      const int i = lane & 15, g16 = lane >> 4;
+      const int col = wrow + 16 * (g16 & 1) + 4 * (i & 3);
+      const int k = 8 * (g16 >> 1) + (i >> 2);
+#pragma unroll
+      for (int f = 0; f < 4; ++f)  // fragment f lies 32 columns further
+        frag_mn[f] = k * 512 + ((((col + 32 * f) >> 3) ^ (4 * (i >> 2))) << 4) + (col & 7) * 2;
+      frag_off = 0;
+      ks_off[0] = 0;
+      ks_off[1] = 16 * 512;
+      kstep = BK * ld * 2;
+    }
+  }
+  // fragment f (32 rows further per f) of k-step ks from stage base s
+  __device__ __forceinline__ bf16x8 fetch(const unsigned char* s, int f, int ks) const {
+    if (!MN) {
+      return *reinterpret_cast<const bf16x8*>(s + frag_off + f * 32 * (BK * 2) + ks_off[ks]);
+    } else {
+      const unsigned char* p = s + frag_mn[f] + ks_off[ks];
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 4 * 512));
+      const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      return __builtin_bit_cast(bf16x8, v);
+    }
+  }
+};
+
+template <int KIND, bool A_MN, bool B_MN, bool SYM>
+__global__ void __launch_bounds__(NTH) sm_ns_gemm_pipe_kernel(const sm_gemm_args args) {
+  __shared__ __attribute__((aligned(1024))) unsigned char sA0[OPB], sA1[OPB], sA2[OPB], sA3[OPB];
+  __shared__ __attribute__((aligned(1024))) unsigned char sB0[OPB], sB1[OPB], sB2[OPB], sB3[OPB];
+
+  // ---- which tile
+  const int wg = blockIdx.x;
+  const int L = (wg & 7) * args.tiles_per_xcd + (wg >> 3);
+  if (L >= args.total_tiles) return;
+  int pi = 0;
+  while (pi + 1 < args.n_prob && L >= args.p[pi + 1].tile_begin) ++pi;
+  const sm_gemm_prob& P = args.p[pi];
+  int t = L - P.tile_begin;
+  const int per_batch = SYM ? P.tiles_m * (P.tiles_m + 1) / 2 : P.tiles_m * P.tiles_n;
+  const int b = t / per_batch;
+  t -= b * per_batch;
+  int tm, tn;
+  if (SYM) {  // upper triangle, column by column: (0,0) (0,1) (1,1) (0,2) ...
+    tn = 0;
+    while (t > tn) {
+      t -= tn + 1;
+      ++tn;
+    }
+    tm = t;
+  } else {
+    tn = t / P.tiles_m;
+    tm = t - tn * P.tiles_m;
+  }
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int M = P.M, N = P.N, K = P.K;
+  const bf16_t* __restrict__ A = P.A + (long long)b * P.sA;
+  const bf16_t* __restrict__ B = P.B + (long long)b * P.sB;
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int w_m = wv & 1, w_n = wv >> 1;
+
+  // ---- global -> LDS: 16 wave-loads per operand slice; this wave issues two of A and two of B.
+  // Buffer loads: the per-lane byte offset is fixed for the whole K walk, the slice offset is scalar.
+  const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A), 0, 0x7FFFFFFF, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(B), 0, 0x7FFFFFFF, 0x00020000);
+  operand_lane<A_MN> oa;
+  operand_lane<B_MN> ob;
+  oa.init(lane, wv, m0, M, P.lda, w_m * WM);
+  ob.init(lane, wv, n0, N, P.ldb, w_n * WN);
+  // plain locals: the buffer-load builtin is not instantiated on the host side when its
+  // operands are member expressions of a dependent type
+  const int va0 = oa.voff[0], va1 = oa.voff[1], vb0 = ob.voff[0], vb1 = ob.voff[1], ksa = oa.kstep, ksb = ob.kstep;
+#define ISSUE(sa, sb, slice)                                                                                          \
+  {                                                                                                                   \
+    _Pragma("unroll") for (int q = 0; q < 2; ++q) {                                                                   \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, LDS_PTR((sa) + (2 * wv + q) * 1024), 16, q ? va1 : va0,               \
+                                               (slice) * ksa, 0, 0);                                             \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, LDS_PTR((sb) + (2 * wv + q) * 1024), 16, q ? vb1 : vb0,               \
+                                               (slice) * ksb, 0, 0);                                             \
+    }                                                                                                                 \
+  }
+
+  f32x16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // two fragment sets: while the matrix pipe works through one, the LDS reads of the other are in flight
+  bf16x8 fa[2][FM], fb[2][FN];
+#define FETCH(set, sa, sb, ks)                                                          \
+  {                                                                                     \
+    _Pragma("unroll") for (int i = 0; i < FM; ++i) fa[set][i] = oa.fetch(sa, i, ks);    \
+    _Pragma("unroll") for (int j = 0; j < FN; ++j) fb[set][j] = ob.fetch(sb, j, ks);    \
+  }
+#define MMA(set)                                                                                                \
+  {                                                                                                             \
+    _Pragma("unroll") for (int i = 0; i < FM; ++i) _Pragma("unroll") for (int j = 0; j < FN; ++j) acc[i][j] =   \
+        __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);                    \
+  }
+
+  const int nk = K / BK;
+  int kt = 0;
+  // Leftover slices (nk mod 4) first, one at a time through stage 0, so that the ring below
+  // always runs whole turns.
+  for (const int rem = nk & 3; kt < rem; ++kt) {
+    ISSUE(sA0, sB0, kt);
+    __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0) */
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    FETCH(0, sA0, sB0, 0);
+    FETCH(1, sA0, sB0, 1);
+    MMA(0);
+    MMA(1);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+  }
+  if (kt < nk) {
+    // One ring step.  On entry fragment set 0 holds (slice kt, ks 0); (na, nb) holds slice kt + 1,
+    // already resident; slice kt + 3 goes to (ia, ib).  Order inside a step: start the LDS reads of
+    // the next fragment set, then feed the matrix pipe with the set that is ready.  Past the end
+    // the issue re-reads the last slice (never consumed) so every step has the same shape: after
+    // the wait at most the 4 newest loads of this wave are still in flight.
+#define RING_STEP(ca, cb, na, nb, ia, ib)                         \
+  {                                                               \
+    ISSUE(ia, ib, min(kt + 3, nk - 1));                           \
+    FETCH(1, ca, cb, 1);                                          \
+    __builtin_amdgcn_sched_barrier(0);                            \
+    MMA(0);                                                       \
+    __builtin_amdgcn_sched_barrier(0);                            \
+    FETCH(0, na, nb, 0);                                          \
+    __builtin_amdgcn_sched_barrier(0);                            \
+    MMA(1);                                                       \
+    __builtin_amdgcn_sched_barrier(0);                            \
+    __builtin_amdgcn_s_waitcnt(0x0F74); /* vmcnt(4) */            \
+    __builtin_amdgcn_s_barrier();                                 \
+    asm volatile("" ::: "memory");                                \
+    ++kt;                                                         \
+  }
+    ISSUE(sA0, sB0, kt);
+    ISSUE(sA1, sB1, min(kt + 1, nk - 1));
+    ISSUE(sA2, sB2, min(kt + 2, nk - 1));
+    __builtin_amdgcn_s_waitcnt(0x0F74); /* vmcnt(4) */
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    FETCH(0, sA0, sB0, 0);
+    do {
+      RING_STEP(sA0, sB0, sA1, sB1, sA3, sB3);
+      RING_STEP(sA1, sB1, sA2, sB2, sA0, sB0);
+      RING_STEP(sA2, sB2, sA3, sB3, sA1, sB1);
+      RING_STEP(sA3, sB3, sA0, sB0, sA2, sB2);
+    } while (kt < nk);
+#undef RING_STEP
+    __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0) */
+  }
+#undef FETCH
+#undef MMA
+#undef ISSUE
+
+  // ---- epilogue straight from the accumulators: a lane holds row m and 4 consecutive columns
+  float s = 1.f;
+  if (P.scale && args.scale_pow) {
+    s = P.scale[b];
+    if (args.scale_pow == 2) s *= s;
+  }
+  const float alpha = args.alpha * s;
+  const bf16_t* __restrict__ R = P.R ? P.R + (long long)b * P.sC : nullptr;
+  bf16_t* __restrict__ C = P.C + (long long)b * P.sC;
+  const int fr = lane & 31, fg = lane >> 5;
+  const bool mirror = SYM && (tm != tn);
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+    const int mg = m0 + w_m * WM + i * 32 + fr;
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+#pragma unroll
+      for (int vg = 0; vg < 4; ++vg) {
+        const int ng = n0 + w_n * WN + j * 32 + 8 * vg + 4 * fg;
+        if (mg >= M || ng >= N) continue;
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          o[e] = alpha * acc[i][j][4 * vg + e];
+          if (mg == ng + e) o[e] += args.diag;
+        }
+        if (R) {
+          const bf16x4 rv = *reinterpret_cast<const bf16x4*>(R + (long long)mg * P.ldc + ng);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] += args.gamma * (float)rv[e];
+        }
+        const bf16x4 h = {(bf16_t)o[0], (bf16_t)o[1], (bf16_t)o[2], (bf16_t)o[3]};
+        *reinterpret_cast<bf16x4*>(C + (long long)mg * P.ldc + ng) = h;
+        if (mirror) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) C[(long long)(ng + e) * P.ldc + mg] = h[e];
+        }
+      }
+    }
+  }
+}
+
+// tile bookkeeping shared by every instantiation
+static void fill_tiles(sm_gemm_args& args, bool sym) {
+  int total = 0;
+  for (int i = 0; i < args.n_prob; ++i) {
+    sm_gemm_prob& P = args.p[i];
+    P.tiles_m = (P.M + BM - 1) / BM;
+    P.tiles_n = (P.N + BN - 1) / BN;
+    P.tile_begin = total;
+    total += (sym ? P.tiles_m * (P.tiles_m + 1) / 2 : P.tiles_m * P.tiles_n) * P.batch;
+  }
+  args.total_tiles = total;
+  args.tiles_per_xcd = (total + 7) / 8;
+}
+
+}  // namespace sm_pipe
+using namespace sm_pipe;
+
+// layout: bit 0 = A is MN-contiguous, bit 1 = B is MN-contiguous.  sym: C symmetric (A == B).
+// Supported combinations are the four the iteration needs (see the header of this file).
+int sm_launch_gemm_pipe(signmuon_ctx* ctx, sm_gemm_args& args, int klass, int layout, bool sym) {
+  for (int i = 0; i < args.n_prob; ++i) {
+    const sm_gemm_prob& P = args.p[i];
+    if (P.M % 64 || P.N % 64 || P.K % 32 || P.lda % 8 || P.ldb % 8 || P.ldc % 8 || !sm_aligned(P.A, 16) ||
+        !sm_aligned(P.B, 16) || !sm_aligned(P.C, 16) || P.sA % 8 || P.sB % 8 || P.sC % 8 || (sym && P.M != P.N))
+      return sm_fail(ctx, SM_EINVAL, "internal: GEMM operand not padded/aligned");
+    // buffer offsets are 32-bit
+    const long long a_ext = (layout & 1) ? (long long)P.K * P.lda : (long long)P.M * P.lda;
+    const long long b_ext = (layout & 2) ? (long long)P.K * P.ldb : (long long)P.N * P.ldb;
+    if (a_ext * 2 >= 0x7FFFFFFFLL || b_ext * 2 >= 0x7FFFFFFFLL)
+      return sm_fail(ctx, SM_EUNSUPPORTED, "internal: GEMM operand larger than 2 GiB");
+  }
+  fill_tiles(args, sym);
+  if (args.total_tiles == 0) return SM_OK;
+  const dim3 grid(args.tiles_per_xcd * 8), block(NTH);
+  const bool gram = (klass == SM_K_NS_GRAM);
+  {
+    sm_launch_scope sc(ctx, klass);
+    if (gram && layout == 0 && sym)
+      hipLaunchKernelGGL((sm_ns_gemm_pipe_kernel<0, false, false, true>), grid, block, 0, ctx->stream, args);
+    else if (gram && layout == 3 && sym)
+      hipLaunchKernelGGL((sm_ns_gemm_pipe_kernel<0, true, true, true>), grid, block, 0, ctx->stream, args);
+    else if (gram && layout == 0 && !sym)
+      hipLaunchKernelGGL((sm_ns_gemm_pipe_kernel<0, false, false, false>), grid, block, 0, ctx->stream, args);
+    else if (!gram && layout == 0 && !sym)
+      hipLaunchKernelGGL((sm_ns_gemm_pipe_kernel<1, false, false, false>), grid, block, 0, ctx->stream, args);
+    else if (!gram && layout == 2 && !sym)
+      hipLaunchKernelGGL((sm_ns_gemm_pipe_kernel<1, false, true, false>), grid, block, 0, ctx->stream, args);
+    else
+      return sm_fail(ctx, SM_EUNSUPPORTED, "internal: GEMM layout combination not built");
+  }
+  SM_HIP(ctx, hipGetLastError());
+  return SM_OK;
+}
