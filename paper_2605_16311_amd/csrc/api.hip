@@ -132,101 +132,95 @@ int get_plan(signmuon_ctx* ctx, int n, const int* rows, const int* cols, int M, 
 // Runs `steps` Newton-Schulz steps on every class, batch = count * mult per class,
 // starting from buffer `cur` (0/1) of each class.  Scales the first step by the
 // per-item inv_sigma when use_scale.  Returns the buffer index holding the result.
-// Per step: one Gram launch and one apply launch for the classes with rows <= cols
-// (Gram over the rows: Bm = a I + b Y Y^T, Y' = Bm Y) and one of each for the others
-// (Gram over the columns: Bm = a I + b Y^T Y, Y' = Y Bm).  Y is read in place in both.
+// Per step: one Gram launch and one apply launch over all classes.  Classes with rows <= cols
+// take the Gram over the rows (Bm = a I + b Y Y^T, Y' = Bm Y), the others over the columns
+// (Bm = a I + b Y^T Y, Y' = Y Bm).  Y is read in place in both.
 int run_ns(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coeffs, bool use_scale, int* cur_io) {
   int cur = *cur_io;
   const float a = coeffs[0], b = coeffs[1], c = coeffs[2];
   for (int k = 0; k < steps; ++k) {
     const bool sc = use_scale && k == 0;
     for (int phase = 0; phase < 2; ++phase) {      // 0: Gram, 1: apply
-      for (int wide = 1; wide >= 0; --wide) {
-        std::vector<ns_class*> group;
-        for (auto& cl : pl->classes)
-          if ((int)cl.wide == wide) group.push_back(&cl);
-        for (size_t c0 = 0; c0 < group.size(); c0 += SM_GEMM_MAX_PROB) {
-          const int g = (int)std::min(group.size() - c0, (size_t)SM_GEMM_MAX_PROB);
-          sm_gemm_args ga;
-          ga.n_prob = g;
-          ga.pad_ = 0;
-          ga.gamma = 0.f;
-          if (phase == 0) {
-            ga.scale_pow = sc ? 2 : 0;
-            ga.alpha = (c != 0.f) ? 1.f : b;
-            ga.diag = (c != 0.f) ? 0.f : a;
+      const size_t ncls = pl->classes.size();
+      for (size_t c0 = 0; c0 < ncls; c0 += SM_GEMM_MAX_PROB) {
+        const int g = (int)std::min(ncls - c0, (size_t)SM_GEMM_MAX_PROB);
+        sm_gemm_args ga;
+        ga.n_prob = g;
+        ga.pad_ = 0;
+        ga.gamma = 0.f;
+        if (phase == 0) {
+          ga.scale_pow = sc ? 2 : 0;
+          ga.alpha = (c != 0.f) ? 1.f : b;
+          ga.diag = (c != 0.f) ? 0.f : a;
+        } else {
+          ga.scale_pow = sc ? 1 : 0;
+          ga.alpha = 1.f;
+          ga.diag = 0.f;
+        }
+        for (int i = 0; i < g; ++i) {
+          ns_class& cl = pl->classes[c0 + i];
+          sm_gemm_prob& P = ga.p[i];
+          bf16_t* y = at<bf16_t>(ctx, cl.off_x[cur]);
+          bf16_t* bm = at<bf16_t>(ctx, cl.off_b);
+          const long long ss = (long long)cl.s * cl.s;
+          P.R = nullptr;
+          P.scale = sc ? at<float>(ctx, cl.off_inv) : nullptr;
+          P.batch = cl.count * mult;
+          if (phase == 0) {  // C[s][s] from Y: rows of Y (wide, K-contiguous) or columns of Y (tall)
+            P.A = P.B = y;
+            P.C = (c != 0.f) ? at<bf16_t>(ctx, cl.off_a) : bm;
+            P.sA = P.sB = cl.mat;
+            P.sC = ss;
+            P.M = P.N = cl.s;
+            P.K = cl.l;
+            P.lda = P.ldb = cl.cp;
+            P.ldc = cl.s;
+            P.layout = cl.wide ? 0 : 3;
           } else {
-            ga.scale_pow = sc ? 1 : 0;
-            ga.alpha = 1.f;
-            ga.diag = 0.f;
+            P.C = at<bf16_t>(ctx, cl.off_x[cur ^ 1]);
+            P.sC = cl.mat;
+            P.M = cl.rp;
+            P.N = cl.cp;
+            P.ldc = cl.cp;
+            P.K = cl.s;
+            if (cl.wide) {  // Y'[rp][cp] = Bm[rp][rp] * Y[rp][cp]: second operand is [K][N]
+              P.A = bm;
+              P.B = y;
+              P.sA = ss;
+              P.sB = cl.mat;
+              P.lda = cl.s;
+              P.ldb = cl.cp;
+              P.layout = 2;
+            } else {        // Y'[rp][cp] = Y[rp][cp] * Bm[cp][cp]^T, Bm symmetric
+              P.A = y;
+              P.B = bm;
+              P.sA = cl.mat;
+              P.sB = ss;
+              P.lda = cl.cp;
+              P.ldb = cl.s;
+              P.layout = 0;
+            }
           }
+        }
+        int rc = sm_launch_gemm_pipe(ctx, ga, phase == 0 ? SM_K_NS_GRAM : SM_K_NS_APPLY);
+        if (rc != SM_OK) return rc;
+        if (phase == 0 && c != 0.f) {  // Bm = c A A^T + b A + a I   (A symmetric)
+          ga.scale_pow = 0;
+          ga.alpha = c;
+          ga.gamma = b;
+          ga.diag = a;
           for (int i = 0; i < g; ++i) {
-            ns_class& cl = *group[c0 + i];
+            ns_class& cl = pl->classes[c0 + i];
             sm_gemm_prob& P = ga.p[i];
-            bf16_t* y = at<bf16_t>(ctx, cl.off_x[cur]);
-            bf16_t* bm = at<bf16_t>(ctx, cl.off_b);
-            const long long ss = (long long)cl.s * cl.s;
-            P.R = nullptr;
-            P.scale = sc ? at<float>(ctx, cl.off_inv) : nullptr;
-            P.batch = cl.count * mult;
-            P.pad_ = 0;
-            if (phase == 0) {  // C[s][s] from Y: rows of Y (wide, K-contiguous) or columns of Y (tall)
-              P.A = P.B = y;
-              P.C = (c != 0.f) ? at<bf16_t>(ctx, cl.off_a) : bm;
-              P.sA = P.sB = cl.mat;
-              P.sC = ss;
-              P.M = P.N = cl.s;
-              P.K = cl.l;
-              P.lda = P.ldb = cl.cp;
-              P.ldc = cl.s;
-            } else {
-              P.C = at<bf16_t>(ctx, cl.off_x[cur ^ 1]);
-              P.sC = cl.mat;
-              P.M = cl.rp;
-              P.N = cl.cp;
-              P.ldc = cl.cp;
-              P.K = cl.s;
-              if (wide) {  // Y'[rp][cp] = Bm[rp][rp] * Y[rp][cp]: second operand is [K][N]
-                P.A = bm;
-                P.B = y;
-                P.sA = ss;
-                P.sB = cl.mat;
-                P.lda = cl.s;
-                P.ldb = cl.cp;
-              } else {     // Y'[rp][cp] = Y[rp][cp] * Bm[cp][cp]^T, Bm symmetric
-                P.A = y;
-                P.B = bm;
-                P.sA = cl.mat;
-                P.sB = ss;
-                P.lda = cl.cp;
-                P.ldb = cl.s;
-              }
-            }
+            P.A = P.B = P.R = at<bf16_t>(ctx, cl.off_a);
+            P.C = at<bf16_t>(ctx, cl.off_b);
+            P.scale = nullptr;
+            P.sA = P.sB = P.sC = (long long)cl.s * cl.s;
+            P.M = P.N = P.K = cl.s;
+            P.lda = P.ldb = P.ldc = cl.s;
+            P.layout = 0;
           }
-          int rc;
-          if (phase == 0) {
-            rc = sm_launch_gemm_pipe(ctx, ga, SM_K_NS_GRAM, wide ? 0 : 3, true);
-            if (rc != SM_OK) return rc;
-            if (c != 0.f) {  // Bm = c A A^T + b A + a I   (A symmetric)
-              ga.scale_pow = 0;
-              ga.alpha = c;
-              ga.gamma = b;
-              ga.diag = a;
-              for (int i = 0; i < g; ++i) {
-                ns_class& cl = *group[c0 + i];
-                sm_gemm_prob& P = ga.p[i];
-                P.A = P.B = P.R = at<bf16_t>(ctx, cl.off_a);
-                P.C = at<bf16_t>(ctx, cl.off_b);
-                P.scale = nullptr;
-                P.sA = P.sB = P.sC = (long long)cl.s * cl.s;
-                P.M = P.N = P.K = cl.s;
-                P.lda = P.ldb = P.ldc = cl.s;
-              }
-              rc = sm_launch_gemm_pipe(ctx, ga, SM_K_NS_GRAM, 0, true);
-            }
-          } else {
-            rc = sm_launch_gemm_pipe(ctx, ga, SM_K_NS_APPLY, wide ? 2 : 0, false);
-          }
+          rc = sm_launch_gemm_pipe(ctx, ga, SM_K_NS_GRAM);
           if (rc != SM_OK) return rc;
         }
       }

@@ -138,7 +138,7 @@ struct sm_gemm_prob {
   int batch;
   int tiles_m, tiles_n;
   int tile_begin;
-  int pad_;
+  int layout;            // pipelined kernel only; bit 0: A stored [K][M], bit 1: B stored [K][N]
 };
 constexpr int SM_GEMM_MAX_PROB = 32;
 struct sm_gemm_args {
@@ -153,10 +153,11 @@ struct sm_gemm_args {
 // Fills tiles_m/tiles_n/tile_begin/total_tiles and launches; klass is SM_K_NS_GRAM or SM_K_NS_APPLY.
 // Register-staged kernel, both operands K-contiguous (kept as the reference implementation).
 int sm_launch_gemm_nt(signmuon_ctx* ctx, sm_gemm_args& args, int klass);
-// Pipelined kernel.  layout bit 0: A is stored [K][M]; bit 1: B is stored [K][N] (lda/ldb are then
-// the row lengths of those arrays).  sym: A == B, only the upper triangle of tiles is computed and
-// mirrored.  K must be a multiple of 32.
-int sm_launch_gemm_pipe(signmuon_ctx* ctx, sm_gemm_args& args, int klass, int layout, bool sym);
+// Pipelined kernel.  Per problem, layout bit 0: A is stored [K][M]; bit 1: B is stored [K][N]
+// (lda/ldb are then the row lengths of those arrays).  SM_K_NS_GRAM: A == B, layout 0 or 3, only
+// the upper triangle of tiles is computed and mirrored.  SM_K_NS_APPLY: layout 0 or 2.
+// K must be a multiple of 32.
+int sm_launch_gemm_pipe(signmuon_ctx* ctx, sm_gemm_args& args, int klass);
 
 // ---------------------------------------------------------------- power iteration (poweriter.hip)
 // sigma[b] = PowerIter(X[b], P, eps, v0[b]); X bf16 [rows][ld]; scratch: (rows + 2*cols + 4) floats per batch

@@ -8,23 +8,25 @@
 //   Gram,  rows >  cols : A = B = Y           (MN, MN)   symmetric output
 //   apply, rows <= cols : A = Bm, B = Y       (KC, MN)   Y' = Bm Y
 //   apply, rows >  cols : A = Y,  B = Bm      (KC, KC)   Y' = Y Bm   (Bm symmetric)
-// so Y is only ever read in its own row-major layout and no transposed copy exists.
+// so Y is only ever read in its own row-major layout and no transposed copy exists.  The
+// layout is a per-problem flag: one launch covers every matrix of a half-step, whatever its
+// orientation.
 //
-// Structure.  A workgroup of 8 waves (2 per SIMD) owns a 256 x 256 tile of C; each wave a
-// 128 x 64 sub-tile held as 4 x 2 accumulators of v_mfma_f32_32x32x16_bf16.  K advances in
-// slices of 32.  Slices travel global -> LDS with buffer_load_dwordx4 ... lds (no staging
-// registers) into a ring of four stages: while slice t is multiplied, slice t+1 is already
-// resident (its first fragments are fetched before the barrier, so the matrix pipe does not
-// drain), slice t+2 is landing and slice t+3 is being issued.  One barrier per slice, preceded
-// by a vmcnt wait that leaves only the newest slice in flight.  Each stage is its own
-// __shared__ array so the compiler can tell the LDS reads of one stage from the pending
-// global->LDS writes of another.
+// Structure.  A workgroup of 8 waves (2 per SIMD) owns a TS x TS tile of C (TS = 256, or 128
+// when there is too little work for 256 CUs); each wave a (TS/2) x (TS/4) sub-tile held as
+// accumulators of v_mfma_f32_32x32x16_bf16.  K advances in slices of 32.  Slices travel
+// global -> LDS with buffer_load_dwordx4 ... lds (no staging registers) into a ring of four
+// stages: while slice t is multiplied, slice t+1 is already resident (its first fragments are
+// fetched before the barrier, so the matrix pipe does not drain), slice t+2 is landing and
+// slice t+3 is being issued.  One barrier per slice, preceded by a vmcnt wait that leaves only
+// the newest slice in flight.  Each stage is its own __shared__ array so the compiler can tell
+// the LDS reads of one stage from the pending global->LDS writes of another.
 //
-// LDS layouts (16 KiB per operand slice).  The LDS serves a 16-byte read sixteen lanes at a
-// time, one 16-byte bank group per lane, and an 8-byte read thirty-two lanes at a time:
-//   KC: 256 rows of 64 bytes; chunk c of row r sits at slot c ^ ((r >> 2) & 3); fragments are
+// LDS layouts (TS * 64 bytes per operand slice).  The LDS serves a 16-byte read sixteen lanes
+// at a time, one 16-byte bank group per lane, and an 8-byte read thirty-two lanes at a time:
+//   KC: TS rows of 64 bytes; chunk c of row r sits at slot c ^ ((r >> 2) & 3); fragments are
 //       read with ds_read_b128.
-//   MN: 32 k-rows of 512 bytes; 16-byte chunk c of k-row k sits at slot c ^ (4 (k & 3));
+//   MN: 32 k-rows of 2 TS bytes; 16-byte chunk c of k-row k sits at slot c ^ (4 (k & 3));
 //       fragments are read with ds_read_b64_tr_b16, which hands lane i of a 16-lane group
 //       column i of the 4 x 16 block whose rows the group's lanes address.
 // The global->LDS load writes its 64 lanes in order, so each lane fetches the chunk that
@@ -36,29 +38,29 @@
 
 namespace sm_pipe {
 
-constexpr int BM = 256, BN = 256, BK = 32, NTH = 512;
-constexpr int WM = 128, WN = 64, FM = 4, FN = 2;
-constexpr int OPB = 256 * BK * 2;  // bytes of one operand slice: 16 KiB
+constexpr int BK = 32, NTH = 512;
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
 // Per-lane constants of one operand: where its global->LDS loads read, where its fragments sit.
-template <bool MN>
+template <bool MN, int TS>
 struct operand_lane {
-  int voff[2];    // byte offset of this lane's two wave-loads inside the operand (slice offset is scalar)
-  int frag_off;   // KC: LDS byte offset of fragment 0 (ks = 0) for this lane
-  int frag_mn[4]; // MN: LDS byte offset of fragment f (ks = 0, first half) for this lane
-  int ks_off[2];  // offset of k-step 0, 1 inside the slice
-  int kstep;      // scalar byte step per K slice
+  static constexpr int NLOAD = TS / 128;  // wave-loads of this operand per wave and slice
+  static constexpr int ROWB = TS * 2;     // MN: bytes per k-row
+  int voff[NLOAD];  // byte offset of this lane's wave-loads inside the operand (slice offset is scalar)
+  int frag_off;     // KC: LDS byte offset of fragment 0 (ks = 0) for this lane
+  int frag_mn[4];   // MN: LDS byte offset of fragment f (ks = 0, first half) for this lane
+  int ks_off[2];    // offset of k-step 0, 1 inside the slice
+  int kstep;        // scalar byte step per K slice
 
   // row0: first tile row of the workgroup; wrow: first row of this wave's sub-tile inside the tile
   __device__ __forceinline__ void init(int lane, int wv, int row0, int rows, int ld, int wrow) {
     if (!MN) {
 #pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        const int row = 16 * (2 * wv + q) + (lane >> 2);
+      for (int q = 0; q < NLOAD; ++q) {
+        const int row = 16 * (NLOAD * wv + q) + (lane >> 2);
         const int chunk = (lane & 3) ^ ((row >> 2) & 3);
         voff[q] = (min(row0 + row, rows - 1) * ld + chunk * 8) * 2;
       }
@@ -68,10 +70,12 @@ struct operand_lane {
       ks_off[1] = ((2 + fg) ^ fsw) * 16;
       kstep = BK * 2;
     } else {
+      constexpr int LPR = ROWB / 16;   // lanes (16-byte chunks) per k-row
+      constexpr int KPL = 64 / LPR;    // k-rows per wave-load
 #pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        const int k = 2 * (2 * wv + q) + (lane >> 5);
-        const int chunk = (lane & 31) ^ (4 * (k & 3));
+      for (int q = 0; q < NLOAD; ++q) {
+        const int k = KPL * (NLOAD * wv + q) + lane / LPR;
+        const int chunk = (lane % LPR) ^ (4 * (k & 3));
         voff[q] = (k * ld + min(row0 + chunk * 8, rows - 8)) * 2;
       }
       // transposed read: 16-lane group g16, lane i in it; the group covers columns 16 (g16 & 1) ..+15
@@ -81,10 +85,10 @@ struct operand_lane {
       const int k = 8 * (g16 >> 1) + (i >> 2);
 #pragma unroll
       for (int f = 0; f < 4; ++f)  // fragment f lies 32 columns further
-        frag_mn[f] = k * 512 + ((((col + 32 * f) >> 3) ^ (4 * (i >> 2))) << 4) + (col & 7) * 2;
+        frag_mn[f] = k * ROWB + ((((col + 32 * f) >> 3) ^ (4 * (i >> 2))) << 4) + (col & 7) * 2;
       frag_off = 0;
       ks_off[0] = 0;
-      ks_off[1] = 16 * 512;
+      ks_off[1] = 16 * ROWB;
       kstep = BK * ld * 2;
     }
   }
@@ -95,42 +99,25 @@ struct operand_lane {
     } else {
       const unsigned char* p = s + frag_mn[f] + ks_off[ks];
       const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
-      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 4 * 512));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 4 * ROWB));
       const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
       return __builtin_bit_cast(bf16x8, v);
     }
   }
 };
 
-template <int KIND, bool A_MN, bool B_MN, bool SYM>
-__global__ void __launch_bounds__(NTH) sm_ns_gemm_pipe_kernel(const sm_gemm_args args) {
-  __shared__ __attribute__((aligned(1024))) unsigned char sA0[OPB], sA1[OPB], sA2[OPB], sA3[OPB];
-  __shared__ __attribute__((aligned(1024))) unsigned char sB0[OPB], sB1[OPB], sB2[OPB], sB3[OPB];
-
-  // ---- which tile
-  const int wg = blockIdx.x;
-  const int L = (wg & 7) * args.tiles_per_xcd + (wg >> 3);
-  if (L >= args.total_tiles) return;
-  int pi = 0;
-  while (pi + 1 < args.n_prob && L >= args.p[pi + 1].tile_begin) ++pi;
-  const sm_gemm_prob& P = args.p[pi];
-  int t = L - P.tile_begin;
-  const int per_batch = SYM ? P.tiles_m * (P.tiles_m + 1) / 2 : P.tiles_m * P.tiles_n;
-  const int b = t / per_batch;
-  t -= b * per_batch;
-  int tm, tn;
-  if (SYM) {  // upper triangle, column by column: (0,0) (0,1) (1,1) (0,2) ...
-    tn = 0;
-    while (t > tn) {
-      t -= tn + 1;
-      ++tn;
-    }
-    tm = t;
-  } else {
-    tn = t / P.tiles_m;
-    tm = t - tn * P.tiles_m;
-  }
-  const int m0 = tm * BM, n0 = tn * BN;
+// One TS x TS tile of one problem.  The eight stage arrays are the kernel's own __shared__
+// variables, passed by reference so that every access keeps its identity after inlining.
+template <int TS, bool A_MN, bool B_MN, bool SYM>
+__device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gemm_prob& P, int b, int tm, int tn,
+                                          unsigned char (&sA0)[TS * 64], unsigned char (&sA1)[TS * 64],
+                                          unsigned char (&sA2)[TS * 64], unsigned char (&sA3)[TS * 64],
+                                          unsigned char (&sB0)[TS * 64], unsigned char (&sB1)[TS * 64],
+                                          unsigned char (&sB2)[TS * 64], unsigned char (&sB3)[TS * 64]) {
+  constexpr int WM = TS / 2, WN = TS / 4, FM = TS / 64, FN = TS / 128, NLOAD = TS / 128;
+  // vmcnt(2 * NLOAD): only the newest slice of this wave may still be in flight
+  constexpr int WAIT_NEWEST = 0x0F70 | (2 * NLOAD);
+  const int m0 = tm * TS, n0 = tn * TS;
   const int M = P.M, N = P.N, K = P.K;
   const bf16_t* __restrict__ A = P.A + (long long)b * P.sA;
   const bf16_t* __restrict__ B = P.B + (long long)b * P.sB;
@@ -138,24 +125,25 @@ __global__ void __launch_bounds__(NTH) sm_ns_gemm_pipe_kernel(const sm_gemm_args
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int w_m = wv & 1, w_n = wv >> 1;
 
-  // ---- global -> LDS: 16 wave-loads per operand slice; this wave issues two of A and two of B.
+  // ---- global -> LDS: TS/16 wave-loads per operand slice; this wave issues NLOAD of A and of B.
   // Buffer loads: the per-lane byte offset is fixed for the whole K walk, the slice offset is scalar.
   const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A), 0, 0x7FFFFFFF, 0x00020000);
   const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(B), 0, 0x7FFFFFFF, 0x00020000);
-  operand_lane<A_MN> oa;
-  operand_lane<B_MN> ob;
+  operand_lane<A_MN, TS> oa;
+  operand_lane<B_MN, TS> ob;
   oa.init(lane, wv, m0, M, P.lda, w_m * WM);
   ob.init(lane, wv, n0, N, P.ldb, w_n * WN);
   // plain locals: the buffer-load builtin is not instantiated on the host side when its
   // operands are member expressions of a dependent type
-  const int va0 = oa.voff[0], va1 = oa.voff[1], vb0 = ob.voff[0], vb1 = ob.voff[1], ksa = oa.kstep, ksb = ob.kstep;
+  const int va0 = oa.voff[0], va1 = oa.voff[NLOAD - 1], vb0 = ob.voff[0], vb1 = ob.voff[NLOAD - 1];
+  const int ksa = oa.kstep, ksb = ob.kstep;
 #define ISSUE(sa, sb, slice)                                                                                          \
   {                                                                                                                   \
-    _Pragma("unroll") for (int q = 0; q < 2; ++q) {                                                                   \
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, LDS_PTR((sa) + (2 * wv + q) * 1024), 16, q ? va1 : va0,               \
-                                               (slice) * ksa, 0, 0);                                             \
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, LDS_PTR((sb) + (2 * wv + q) * 1024), 16, q ? vb1 : vb0,               \
-                                               (slice) * ksb, 0, 0);                                             \
+    _Pragma("unroll") for (int q = 0; q < NLOAD; ++q) {                                                               \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, LDS_PTR((sa) + (NLOAD * wv + q) * 1024), 16, q ? va1 : va0,        \
+                                               (slice) * ksa, 0, 0);                                                  \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, LDS_PTR((sb) + (NLOAD * wv + q) * 1024), 16, q ? vb1 : vb0,        \
+                                               (slice) * ksb, 0, 0);                                                  \
     }                                                                                                                 \
   }
 
@@ -201,7 +189,7 @@ __global__ void __launch_bounds__(NTH) sm_ns_gemm_pipe_kernel(const sm_gemm_args
     // already resident; slice kt + 3 goes to (ia, ib).  Order inside a step: start the LDS reads of
     // the next fragment set, then feed the matrix pipe with the set that is ready.  Past the end
     // the issue re-reads the last slice (never consumed) so every step has the same shape: after
-    // the wait at most the 4 newest loads of this wave are still in flight.
+    // the wait only the newest loads of this wave are still in flight.
 #define RING_STEP(ca, cb, na, nb, ia, ib)                         \
   {                                                               \
     ISSUE(ia, ib, min(kt + 3, nk - 1));                           \
@@ -213,7 +201,7 @@ __global__ void __launch_bounds__(NTH) sm_ns_gemm_pipe_kernel(const sm_gemm_args
     __builtin_amdgcn_sched_barrier(0);                            \
     MMA(1);                                                       \
     __builtin_amdgcn_sched_barrier(0);                            \
-    __builtin_amdgcn_s_waitcnt(0x0F74); /* vmcnt(4) */            \
+    __builtin_amdgcn_s_waitcnt(WAIT_NEWEST);                      \
     __builtin_amdgcn_s_barrier();                                 \
     asm volatile("" ::: "memory");                                \
     ++kt;                                                         \
@@ -221,7 +209,7 @@ __global__ void __launch_bounds__(NTH) sm_ns_gemm_pipe_kernel(const sm_gemm_args
     ISSUE(sA0, sB0, kt);
     ISSUE(sA1, sB1, min(kt + 1, nk - 1));
     ISSUE(sA2, sB2, min(kt + 2, nk - 1));
-    __builtin_amdgcn_s_waitcnt(0x0F74); /* vmcnt(4) */
+    __builtin_amdgcn_s_waitcnt(WAIT_NEWEST);
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     FETCH(0, sA0, sB0, 0);
@@ -280,13 +268,58 @@ __global__ void __launch_bounds__(NTH) sm_ns_gemm_pipe_kernel(const sm_gemm_args
   }
 }
 
+// KIND 0: Gram half-step (symmetric output; operands both KC or both MN).
+// KIND 1: apply half-step (A is KC; B is KC or MN).
+template <int KIND, int TS>
+__global__ void __launch_bounds__(NTH) sm_ns_gemm_pipe_kernel(const sm_gemm_args args) {
+  constexpr bool SYM = (KIND == 0);
+  __shared__ __attribute__((aligned(1024))) unsigned char sA0[TS * 64], sA1[TS * 64], sA2[TS * 64], sA3[TS * 64];
+  __shared__ __attribute__((aligned(1024))) unsigned char sB0[TS * 64], sB1[TS * 64], sB2[TS * 64], sB3[TS * 64];
+
+  // Workgroup ids are dealt round-robin to the 8 XCDs: renumber so that each XCD walks one
+  // contiguous eighth of the tile list and neighbouring tiles share an L2.
+  const int wg = blockIdx.x;
+  const int L = (wg & 7) * args.tiles_per_xcd + (wg >> 3);
+  if (L >= args.total_tiles) return;
+  int pi = 0;
+  while (pi + 1 < args.n_prob && L >= args.p[pi + 1].tile_begin) ++pi;
+  const sm_gemm_prob& P = args.p[pi];
+  int t = L - P.tile_begin;
+  const int per_batch = SYM ? P.tiles_m * (P.tiles_m + 1) / 2 : P.tiles_m * P.tiles_n;
+  const int b = t / per_batch;
+  t -= b * per_batch;
+  int tm, tn;
+  if (SYM) {  // upper triangle, column by column: (0,0) (0,1) (1,1) (0,2) ...
+    tn = 0;
+    while (t > tn) {
+      t -= tn + 1;
+      ++tn;
+    }
+    tm = t;
+  } else {
+    tn = t / P.tiles_m;
+    tm = t - tn * P.tiles_m;
+  }
+  if (KIND == 0) {
+    if (P.layout == 0)
+      gemm_tile<TS, false, false, true>(args, P, b, tm, tn, sA0, sA1, sA2, sA3, sB0, sB1, sB2, sB3);
+    else
+      gemm_tile<TS, true, true, true>(args, P, b, tm, tn, sA0, sA1, sA2, sA3, sB0, sB1, sB2, sB3);
+  } else {
+    if (P.layout == 0)
+      gemm_tile<TS, false, false, false>(args, P, b, tm, tn, sA0, sA1, sA2, sA3, sB0, sB1, sB2, sB3);
+    else
+      gemm_tile<TS, false, true, false>(args, P, b, tm, tn, sA0, sA1, sA2, sA3, sB0, sB1, sB2, sB3);
+  }
+}
+
 // tile bookkeeping shared by every instantiation
-static void fill_tiles(sm_gemm_args& args, bool sym) {
+static void fill_tiles(sm_gemm_args& args, bool sym, int ts) {
   int total = 0;
   for (int i = 0; i < args.n_prob; ++i) {
     sm_gemm_prob& P = args.p[i];
-    P.tiles_m = (P.M + BM - 1) / BM;
-    P.tiles_n = (P.N + BN - 1) / BN;
+    P.tiles_m = (P.M + ts - 1) / ts;
+    P.tiles_n = (P.N + ts - 1) / ts;
     P.tile_begin = total;
     total += (sym ? P.tiles_m * (P.tiles_m + 1) / 2 : P.tiles_m * P.tiles_n) * P.batch;
   }
@@ -297,38 +330,46 @@ static void fill_tiles(sm_gemm_args& args, bool sym) {
 }  // namespace sm_pipe
 using namespace sm_pipe;
 
-// layout: bit 0 = A is MN-contiguous, bit 1 = B is MN-contiguous.  sym: C symmetric (A == B).
-// Supported combinations are the four the iteration needs (see the header of this file).
-int sm_launch_gemm_pipe(signmuon_ctx* ctx, sm_gemm_args& args, int klass, int layout, bool sym) {
+// Per problem, P.layout bit 0: A is MN-contiguous, bit 1: B is MN-contiguous.  klass SM_K_NS_GRAM:
+// A == B, symmetric output, layout 0 or 3.  klass SM_K_NS_APPLY: layout 0 or 2.
+int sm_launch_gemm_pipe(signmuon_ctx* ctx, sm_gemm_args& args, int klass) {
+  const bool gram = (klass == SM_K_NS_GRAM);
   for (int i = 0; i < args.n_prob; ++i) {
     const sm_gemm_prob& P = args.p[i];
     if (P.M % 64 || P.N % 64 || P.K % 32 || P.lda % 8 || P.ldb % 8 || P.ldc % 8 || !sm_aligned(P.A, 16) ||
-        !sm_aligned(P.B, 16) || !sm_aligned(P.C, 16) || P.sA % 8 || P.sB % 8 || P.sC % 8 || (sym && P.M != P.N))
+        !sm_aligned(P.B, 16) || !sm_aligned(P.C, 16) || P.sA % 8 || P.sB % 8 || P.sC % 8 || (gram && P.M != P.N))
       return sm_fail(ctx, SM_EINVAL, "internal: GEMM operand not padded/aligned");
+    if (gram ? (P.layout != 0 && P.layout != 3) : (P.layout != 0 && P.layout != 2))
+      return sm_fail(ctx, SM_EUNSUPPORTED, "internal: GEMM layout combination not built");
     // buffer offsets are 32-bit
-    const long long a_ext = (layout & 1) ? (long long)P.K * P.lda : (long long)P.M * P.lda;
-    const long long b_ext = (layout & 2) ? (long long)P.K * P.ldb : (long long)P.N * P.ldb;
+    const long long a_ext = (P.layout & 1) ? (long long)P.K * P.lda : (long long)P.M * P.lda;
+    const long long b_ext = (P.layout & 2) ? (long long)P.K * P.ldb : (long long)P.N * P.ldb;
     if (a_ext * 2 >= 0x7FFFFFFFLL || b_ext * 2 >= 0x7FFFFFFFLL)
       return sm_fail(ctx, SM_EUNSUPPORTED, "internal: GEMM operand larger than 2 GiB");
   }
-  fill_tiles(args, sym);
+  static const int env_tile = [] {
+    const char* e = getenv("SIGNMUON_GEMM_TILE");
+    return e ? atoi(e) : 0;
+  }();
+  int ts = env_tile;
+  if (ts != 128 && ts != 256) {
+    // 256 x 256 tiles once there are enough of them to keep 256 CUs busy for several rounds
+    fill_tiles(args, gram, 256);
+    ts = (args.total_tiles >= 1024) ? 256 : 128;
+  }
+  fill_tiles(args, gram, ts);
   if (args.total_tiles == 0) return SM_OK;
   const dim3 grid(args.tiles_per_xcd * 8), block(NTH);
-  const bool gram = (klass == SM_K_NS_GRAM);
   {
     sm_launch_scope sc(ctx, klass);
-    if (gram && layout == 0 && sym)
-      hipLaunchKernelGGL((sm_ns_gemm_pipe_kernel<0, false, false, true>), grid, block, 0, ctx->stream, args);
-    else if (gram && layout == 3 && sym)
-      hipLaunchKernelGGL((sm_ns_gemm_pipe_kernel<0, true, true, true>), grid, block, 0, ctx->stream, args);
-    else if (gram && layout == 0 && !sym)
-      hipLaunchKernelGGL((sm_ns_gemm_pipe_kernel<0, false, false, false>), grid, block, 0, ctx->stream, args);
-    else if (!gram && layout == 0 && !sym)
-      hipLaunchKernelGGL((sm_ns_gemm_pipe_kernel<1, false, false, false>), grid, block, 0, ctx->stream, args);
-    else if (!gram && layout == 2 && !sym)
-      hipLaunchKernelGGL((sm_ns_gemm_pipe_kernel<1, false, true, false>), grid, block, 0, ctx->stream, args);
+    if (gram && ts == 256)
+      hipLaunchKernelGGL((sm_ns_gemm_pipe_kernel<0, 256>), grid, block, 0, ctx->stream, args);
+    else if (gram)
+      hipLaunchKernelGGL((sm_ns_gemm_pipe_kernel<0, 128>), grid, block, 0, ctx->stream, args);
+    else if (ts == 256)
+      hipLaunchKernelGGL((sm_ns_gemm_pipe_kernel<1, 256>), grid, block, 0, ctx->stream, args);
     else
-      return sm_fail(ctx, SM_EUNSUPPORTED, "internal: GEMM layout combination not built");
+      hipLaunchKernelGGL((sm_ns_gemm_pipe_kernel<1, 128>), grid, block, 0, ctx->stream, args);
   }
   SM_HIP(ctx, hipGetLastError());
   return SM_OK;
