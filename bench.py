@@ -136,7 +136,7 @@ def run_workload(name, steps, warmup, torch, P, B):
     return res
 
 
-def cpu_baseline(name, budget_s=25.0):
+def cpu_baseline(name, budget_s=15.0):
     """Times the oracle (float32 variant, as it stands) on a bounded sample of the workload."""
     import numpy as np
     import workloads as wl
@@ -148,39 +148,38 @@ def cpu_baseline(name, budget_s=25.0):
         cores = os.cpu_count() or 1
     cfg = wl.WORKLOADS[name]
     shapes, M = cfg["shapes"], cfg["M"]
-    # distinct shapes with multiplicity; time whole-step work of one block per distinct shape
-    distinct = {}
-    for s in shapes:
-        distinct[s] = distinct.get(s, 0) + 1
-    total = 0.0
-    timed_workers = 0
-    sample_desc = []
-    for (r, c), count in distinct.items():
-        # a worker's share of one block is independent of the others: time a few workers, scale to M
-        mw = M
-        per_worker_flop = cfg["ns_steps"] * 4.0 * min(r, c) ** 2 * max(r, c)
-        while mw > 1 and mw * per_worker_flop > 1.5e11:
-            mw //= 2
-        G = wl.worker_grads(name, 0, r, c, M=mw)
-        W = wl.weights(r, c)
+    # Blocks and workers are independent, so the step time is the sum over blocks.  Blocks of the
+    # workload are timed in order (whole per-block step: momentum, M x PolarNS, pack, vote, local
+    # polar, update) until the time budget is used; the rest is scaled by nominal NS work.
+    def block_flop(r, c):
+        return 4.0 * min(r, c) ** 2 * max(r, c) * (cfg["ns_steps"] * M + cfg["local_polar_steps"])
+    total_flop = sum(block_flop(r, c) for r, c in shapes)
+    # visit one block of every distinct shape first, then the remaining blocks
+    order, seen = [], set()
+    for i, sh in enumerate(shapes):
+        if sh not in seen:
+            seen.add(sh)
+            order.append(i)
+    order += [i for i in range(len(shapes)) if i not in order]
+    t_spent, flop_done, n_done = 0.0, 0.0, 0
+    for i in order:
+        r, c = shapes[i]
+        G = wl.worker_grads(name, i, r, c)
+        W = wl.weights(r, c, block=i)
         mom = np.zeros_like(G)
         t0 = time.perf_counter()
-        out = O.signmuon_step(W, mom, G, beta=0.9, lr=1e-3, ns_steps=cfg["ns_steps"],
-                              sign_fmt=cfg["sign_fmt"], local_polar_steps=0, dtype=np.float32)
-        t_workers = time.perf_counter() - t0
-        t_local = 0.0
-        if cfg["local_polar_steps"]:
-            t0 = time.perf_counter()
-            O.local_polar(out["vote"], cfg["local_polar_steps"], dtype=np.float32)
-            t_local = time.perf_counter() - t0
-        total += count * (t_workers * (M / mw) + t_local)
-        timed_workers += mw
-        sample_desc.append(f"{r}x{c}:{mw}of{M}w")
-        if total > 20 * budget_s and False:
+        O.signmuon_step(W, mom, G, beta=0.9, lr=1e-3, ns_steps=cfg["ns_steps"], sign_fmt=cfg["sign_fmt"],
+                        local_polar_steps=cfg["local_polar_steps"], dtype=np.float32)
+        t_spent += time.perf_counter() - t0
+        flop_done += block_flop(r, c)
+        n_done += 1
+        if t_spent > budget_s and n_done >= len(seen):
             break
-    return {"value": 1.0 / total, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
-            "sample": "float32 oracle, one block per distinct shape (" + ", ".join(sample_desc) +
-                      " workers timed), scaled by block count and M; blocks and workers are independent"}
+    step_s = t_spent * total_flop / flop_done
+    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"float32 oracle (numpy), full per-block step on {n_done} of {len(shapes)} blocks "
+                      f"(every distinct shape, all {M} workers) in {t_spent:.1f} s, scaled to the whole set "
+                      f"by nominal Newton-Schulz work"}
 
 
 def main():
@@ -191,6 +190,9 @@ def main():
     ap.add_argument("--workload", default="nanogpt124m")
     ap.add_argument("--also", default="resnet50", help="second workload reported in the same line ('' to skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first run three 1 GiB device copies (torch): a kernel of known traffic for scaling "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the M workers are a batch dimension); "
@@ -203,6 +205,14 @@ def main():
         print("bench.py: no GPU", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     main_res = run_workload(args.workload, args.steps, args.warmup, torch, P, B)
     also = None
     if args.also and args.also != args.workload:
@@ -223,7 +233,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "M": main_res["M"], "blocks": main_res["n_blocks"],
                    "entries": main_res["entries"], "ns_steps": 5, "scale": "fro"},
-        "roofline": {"kernel": "sm_ns_gemm_nt_kernel (apply)", "bound": "mfma", "achieved": ach,
+        "roofline": {"kernel": "sm_ns_gemm_pipe_kernel<1, 256> (apply half-step)", "bound": "mfma", "achieved": ach,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": (ach / MFMA_BF16_PEAK_TFLOPS) if ach else None, "traffic": traffic,
                      "avg_launch_ms": main_res["ns_apply"]["avg_ms"],

@@ -459,6 +459,10 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
   if (rc != SM_OK) return rc;
 
   const int Kp = s->local_polar_steps;
+  // a5 + a6 (+ a8 when there is no local polar step): one sign-pack launch and one vote launch
+  // over all blocks
+  std::vector<sm_sp_desc> sp(n);
+  std::vector<sm_vote_desc> vd(n);
   for (int i = 0; i < n; ++i) {
     ns_class& cl = pl->classes[pl->class_of[i]];
     const int idx = pl->index_in_class[i];
@@ -469,49 +473,58 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
                               (s->ns_steps == 0 && use_scale) ? at<float>(ctx, cl.off_inv) + (long long)idx * M : nullptr);
       if (rc != SM_OK) return rc;
     }
-    // a5: sign + pack
-    void* signs = (s->signs_out && s->signs_out[i]) ? s->signs_out[i] : at<void>(ctx, pl->off_signs[i]);
-    const long long stride = (s->signs_out && s->signs_out[i])
-                                 ? ((s->sign_fmt == SM_SIGN_INT8) ? d : 8 * ((d + 63) / 64))
-                                 : pl->sign_stride[i];
-    rc = sm_launch_sign_pack(ctx, u, SM_BF16, M, cl.rows, cl.cols, cl.cp, cl.mat, s->sign_fmt, signs, stride);
-    if (rc != SM_OK) return rc;
-    // a6 (+ a8 when there is no local polar step)
+    const bool tap = s->signs_out && s->signs_out[i];
+    void* signs = tap ? s->signs_out[i] : at<void>(ctx, pl->off_signs[i]);
+    const long long stride = tap ? ((s->sign_fmt == SM_SIGN_INT8) ? d : 8 * ((d + 63) / 64)) : pl->sign_stride[i];
+    sm_sp_desc& S = sp[i];
+    S.u = u;
+    S.out = signs;
+    S.n = d;
+    S.batch_stride = cl.mat;
+    S.out_stride = stride;
+    S.bytes_per_row = 0;
+    S.cols = cl.cols;
+    S.ld = cl.cp;
+    S.blocks_per_row = S.block_begin = 0;
     float step = s->lr;
     if (s->update_rsqrt_mn) step = s->lr / sqrtf((float)cl.rows * (float)cl.cols);
-    sm_vote_args v;
-    v.signs = signs;
-    v.fmt = s->sign_fmt;
-    v.M = M;
-    v.n = d;
-    v.stride_bytes = stride;
-    v.counts = (s->counts_out) ? s->counts_out[i] : nullptr;
-    v.lr_scaled = step;
+    sm_vote_desc& V = vd[i];
+    V.signs = signs;
+    V.n = d;
+    V.stride_bytes = stride;
+    V.counts = (s->counts_out) ? s->counts_out[i] : nullptr;
+    V.lr = step;
+    V.M = M;
+    V.block_begin = 0;
     if (Kp == 0) {
-      v.voted = nullptr;
-      v.vfmt = SM_VOTE_BITS;
-      v.cols = v.ld = 1;
-      v.w = s->w[i];
+      V.voted = nullptr;
+      V.vfmt = SM_VOTE_BF16;
+      V.cols = V.ld = 1;
+      V.w = s->w[i];
     } else {
       // the voted +-1 matrix becomes item `idx` of the class's post-vote batch, in the
       // buffer that does not hold the workers' U
-      v.voted = at<bf16_t>(ctx, cl.off_x[cur ^ 1]) + (long long)idx * cl.mat;
-      v.vfmt = SM_VOTE_BF16;
-      v.cols = cl.cols;
-      v.ld = cl.cp;
-      v.w = nullptr;
+      V.voted = at<bf16_t>(ctx, cl.off_x[cur ^ 1]) + (long long)idx * cl.mat;
+      V.vfmt = SM_VOTE_BF16;
+      V.cols = cl.cols;
+      V.ld = cl.cp;
+      V.w = nullptr;
     }
-    rc = sm_launch_vote(ctx, v);
-    if (rc != SM_OK) return rc;
-    if (Kp == 0 && s->d_out && s->d_out[i]) {
-      sm_vote_args t = v;
+  }
+  rc = sm_launch_sign_pack_group(ctx, sp.data(), n, SM_BF16, s->sign_fmt, M);
+  if (rc != SM_OK) return rc;
+  rc = sm_launch_vote_group(ctx, vd.data(), n, s->sign_fmt);
+  if (rc != SM_OK) return rc;
+  if (Kp == 0 && s->d_out) {  // W was already stepped; the tap only re-derives the vote
+    for (int i = 0; i < n; ++i) {
+      if (!s->d_out[i]) continue;
+      sm_vote_desc t = vd[i];
       t.voted = s->d_out[i];
       t.vfmt = SM_VOTE_BF16;
       t.cols = t.ld = 1;
       t.counts = nullptr;
       t.w = nullptr;
-      // W was already stepped; the tap only re-derives the vote
-      rc = sm_launch_vote(ctx, t);
+      rc = sm_launch_vote_group(ctx, &t, 1, s->sign_fmt);
       if (rc != SM_OK) return rc;
     }
   }
@@ -546,20 +559,29 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
   rc = run_ns(ctx, pl, 1, Kp, s->coeffs, use_scale2, &cur);
   if (rc != SM_OK) return rc;
 
-  // a8: W <- W - step * D
+  // a8: W <- W - step * D, one launch over all blocks
+  std::vector<sm_upd_desc> ud(n);
   for (int i = 0; i < n; ++i) {
     ns_class& cl = pl->classes[pl->class_of[i]];
     const int idx = pl->index_in_class[i];
     const bf16_t* dmat = at<bf16_t>(ctx, cl.off_x[cur]) + (long long)idx * cl.mat;
     float step = s->lr;
     if (s->update_rsqrt_mn) step = s->lr / sqrtf((float)cl.rows * (float)cl.cols);
-    rc = sm_launch_update(ctx, s->w[i], dmat, cl.rows, cl.cols, cl.cp, step);
-    if (rc != SM_OK) return rc;
+    ud[i].w = s->w[i];
+    ud[i].d = dmat;
+    ud[i].rows = cl.rows;
+    ud[i].cols = cl.cols;
+    ud[i].ld = cl.cp;
+    ud[i].step = step;
+    ud[i].block_begin = 0;
+    ud[i].pad_ = 0;
     if (s->d_out && s->d_out[i]) {
       rc = sm_launch_copy_out(ctx, dmat, cl.cp, cl.mat, 1, cl.rows, cl.cols, s->d_out[i], SM_BF16, nullptr);
       if (rc != SM_OK) return rc;
     }
   }
+  rc = sm_launch_update_group(ctx, ud.data(), n);
+  if (rc != SM_OK) return rc;
   return SM_OK;
 }
 

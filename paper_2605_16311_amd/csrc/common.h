@@ -88,6 +88,46 @@ int sm_launch_reduce_partials(signmuon_ctx* ctx, const float* partial, int chunk
 // inv_sigma[i] = 1 / max(sqrt(sumsq[i]), eps)   (from_sq) or 1 / max(sumsq[i], eps)
 int sm_launch_inv_sigma(signmuon_ctx* ctx, const float* sig, int count, float eps, bool from_sq, float* inv_sigma);
 
+// Grouped sign pack: one launch over a table of matrices, `M` workers each.
+struct sm_sp_desc {
+  const void* u;            // [M][rows][ld]
+  void* out;                // M rows of out_stride bytes
+  long long n;              // rows * cols
+  long long batch_stride;   // elements between workers in u
+  long long out_stride;     // bytes
+  long long bytes_per_row;  // filled by the launcher
+  int cols, ld;
+  int blocks_per_row, block_begin;  // filled by the launcher
+};
+constexpr int SM_SP_MAX_GROUP = 48;
+int sm_launch_sign_pack_group(signmuon_ctx* ctx, const sm_sp_desc* descs, int n, int dtype, int fmt, int M);
+
+// Grouped expanding vote (+ fused update): one launch over a table of matrices.
+struct sm_vote_desc {
+  const void* signs;
+  long long n, stride_bytes;
+  void* voted;       // non-bit formats only (SM_VOTE_INT8/BF16/F32), or null
+  int32_t* counts;
+  float* w;
+  float lr;
+  int M, vfmt, cols, ld;
+  int block_begin;   // filled by the launcher
+};
+constexpr int SM_VOTE_MAX_GROUP = 48;
+int sm_launch_vote_group(signmuon_ctx* ctx, const sm_vote_desc* descs, int n, int fmt);
+
+// Grouped update after a local polar step: w[r][c] -= step * d[r][ld]
+struct sm_upd_desc {
+  float* w;
+  const bf16_t* d;
+  int rows, cols, ld;
+  float step;
+  int block_begin;   // filled by the launcher
+  int pad_;
+};
+constexpr int SM_UPD_MAX_GROUP = 64;
+int sm_launch_update_group(signmuon_ctx* ctx, const sm_upd_desc* descs, int n);
+
 // sign pack from a (possibly padded) 2-D source: u[batch][rows][ld] -> flat row-major bits
 int sm_launch_sign_pack(signmuon_ctx* ctx, const void* u, int dtype, int batch, int rows, int cols,
                         int ld, long long batch_stride, int fmt, void* out, long long out_stride_bytes);

@@ -133,16 +133,27 @@ __global__ void sm_fill_kernel(float* p, int n, float v) {
 // One thread = one output byte = 8 consecutive entries of the flattened matrix.
 // Source row index / padded leading dimension are resolved per byte (cols % 8 == 0
 // on the fast path so a byte never straddles rows).
+// One launch covers a table of matrices (all workers of each): workgroup -> (matrix, worker, chunk).
+struct sp_args {
+  int n;
+  int pad_;
+  sm_sp_desc d[SM_SP_MAX_GROUP];
+};
+
 template <int DT, int FMT, bool FAST>
-__global__ void __launch_bounds__(TPB) sm_sign_pack_kernel(const void* __restrict__ u, long long n, int cols, int ld,
-                                                           long long batch_stride, void* __restrict__ out,
-                                                           long long out_stride, long long bytes_per_row) {
-  const int b = blockIdx.y;
-  const unsigned short* ub = reinterpret_cast<const unsigned short*>(u) + (DT == SM_BF16 ? (long long)b * batch_stride : 0);
-  const unsigned* uf = reinterpret_cast<const unsigned*>(u) + (DT == SM_F32 ? (long long)b * batch_stride : 0);
-  unsigned char* o = reinterpret_cast<unsigned char*>(out) + (long long)b * out_stride;
+__global__ void __launch_bounds__(TPB) sm_sign_pack_kernel(const sp_args a) {
+  int di = 0;
+  while (di + 1 < a.n && (int)blockIdx.x >= a.d[di + 1].block_begin) ++di;
+  const sm_sp_desc& D = a.d[di];
+  const int local = blockIdx.x - D.block_begin;
+  const int b = local / D.blocks_per_row, bx = local - b * D.blocks_per_row;
+  const long long n = D.n, bytes_per_row = D.bytes_per_row;
+  const int cols = D.cols, ld = D.ld;
+  const unsigned short* ub = reinterpret_cast<const unsigned short*>(D.u) + (DT == SM_BF16 ? (long long)b * D.batch_stride : 0);
+  const unsigned* uf = reinterpret_cast<const unsigned*>(D.u) + (DT == SM_F32 ? (long long)b * D.batch_stride : 0);
+  unsigned char* o = reinterpret_cast<unsigned char*>(D.out) + (long long)b * D.out_stride;
   constexpr int UNROLL = 4;
-  const long long q0 = ((long long)blockIdx.x * UNROLL) * TPB + threadIdx.x;
+  const long long q0 = ((long long)bx * UNROLL) * TPB + threadIdx.x;
 #pragma unroll
   for (int j = 0; j < UNROLL; ++j) {
     const long long q = q0 + (long long)j * TPB;  // byte index
@@ -249,22 +260,22 @@ __global__ void __launch_bounds__(TPB) sm_vote_bits_generic_kernel(const unsigne
   voted[q] = (unsigned char)bits;
 }
 
-struct vote_x_args {
-  const void* signs;
-  long long n, stride_bytes;
-  void* voted;
-  int32_t* counts;
-  float* w;
-  float lr;
-  int M, vfmt, cols, ld;
+typedef sm_vote_desc vote_x_args;
+struct vote_g_args {
+  int n;
+  int pad_;
+  sm_vote_desc d[SM_VOTE_MAX_GROUP];
 };
 
 // Expanding vote: one thread = 4 consecutive entries.  FMT selects the input
 // transport; outputs (voted in a non-bit format, counts, fused W update) are all
 // optional.  n4 = ceil(n/4) threads in total.
 template <int FMT>
-__global__ void __launch_bounds__(TPB) sm_vote_expand_kernel(const vote_x_args a) {
-  const long long t = (long long)blockIdx.x * TPB + threadIdx.x;
+__global__ void __launch_bounds__(TPB) sm_vote_expand_kernel(const vote_g_args g) {
+  int di = 0;
+  while (di + 1 < g.n && (int)blockIdx.x >= g.d[di + 1].block_begin) ++di;
+  const vote_x_args& a = g.d[di];
+  const long long t = (long long)(blockIdx.x - a.block_begin) * TPB + threadIdx.x;
   const long long e0 = t * 4;
   if (e0 >= a.n) return;
   int c[4] = {0, 0, 0, 0};
@@ -381,10 +392,22 @@ __global__ void __launch_bounds__(TPB) sm_vote_int8_bits_kernel(const signed cha
 }
 
 // ------------------------------------------------------------------ update after a local polar step
-__global__ void __launch_bounds__(TPB) sm_update_kernel(float* __restrict__ w, const bf16_t* __restrict__ d, int rows,
-                                                        int cols, int ld, float step) {
-  const long long n = (long long)rows * cols;
-  const long long e0 = ((long long)blockIdx.x * TPB + threadIdx.x) * 4;
+struct upd_args {
+  int n;
+  int pad_;
+  sm_upd_desc d[SM_UPD_MAX_GROUP];
+};
+
+__global__ void __launch_bounds__(TPB) sm_update_kernel(const upd_args g) {
+  int di = 0;
+  while (di + 1 < g.n && (int)blockIdx.x >= g.d[di + 1].block_begin) ++di;
+  const sm_upd_desc& D = g.d[di];
+  float* __restrict__ w = D.w;
+  const bf16_t* __restrict__ d = D.d;
+  const int cols = D.cols, ld = D.ld;
+  const float step = D.step;
+  const long long n = (long long)D.rows * cols;
+  const long long e0 = ((long long)(blockIdx.x - D.block_begin) * TPB + threadIdx.x) * 4;
   if (e0 >= n) return;
   if (e0 + 4 <= n && (cols & 3) == 0) {
     const long long di = (ld == cols) ? e0 : (e0 / cols) * ld + (e0 % cols);
@@ -463,36 +486,66 @@ int sm_launch_fill(signmuon_ctx* ctx, float* p, int n, float v) {
   return SM_OK;
 }
 
+int sm_launch_sign_pack_group(signmuon_ctx* ctx, const sm_sp_desc* descs, int n, int dtype, int fmt, int M) {
+  int done = 0;
+  while (done < n) {
+    const int g = std::min(n - done, SM_SP_MAX_GROUP);
+    sp_args a;
+    a.n = g;
+    a.pad_ = 0;
+    int blocks = 0;
+    bool fast_ok = true;
+    for (int i = 0; i < g; ++i) {
+      sm_sp_desc& D = a.d[i];
+      D = descs[done + i];
+      D.bytes_per_row = (fmt == SM_SIGN_1BIT) ? 8 * ((D.n + 63) / 64) : (D.n + 7) / 8;  // threads per row
+      D.blocks_per_row = (int)((D.bytes_per_row + TPB * 4 - 1) / (TPB * 4));
+      D.block_begin = blocks;
+      blocks += D.blocks_per_row * M;
+      // the fast path reads whole 8-entry groups with 16-byte loads
+      fast_ok = fast_ok && (D.ld == D.cols || (D.cols % 8 == 0 && D.ld % 8 == 0)) && sm_aligned(D.u, 16) &&
+                (D.batch_stride % 8 == 0) &&
+                (fmt == SM_SIGN_1BIT || (sm_aligned(D.out, 8) && D.out_stride % 8 == 0));
+    }
+    if (blocks > 0) {
+      const dim3 grid(blocks);
+      sm_launch_scope sc(ctx, SM_K_SIGN_PACK);
+#define SP_LAUNCH(DT, FMT, FAST) hipLaunchKernelGGL((sm_sign_pack_kernel<DT, FMT, FAST>), grid, dim3(TPB), 0, ctx->stream, a)
+      if (dtype == SM_BF16) {
+        if (fmt == SM_SIGN_1BIT) {
+          if (fast_ok) SP_LAUNCH(SM_BF16, SM_SIGN_1BIT, true); else SP_LAUNCH(SM_BF16, SM_SIGN_1BIT, false);
+        } else {
+          if (fast_ok) SP_LAUNCH(SM_BF16, SM_SIGN_INT8, true); else SP_LAUNCH(SM_BF16, SM_SIGN_INT8, false);
+        }
+      } else {
+        if (fmt == SM_SIGN_1BIT) {
+          if (fast_ok) SP_LAUNCH(SM_F32, SM_SIGN_1BIT, true); else SP_LAUNCH(SM_F32, SM_SIGN_1BIT, false);
+        } else {
+          if (fast_ok) SP_LAUNCH(SM_F32, SM_SIGN_INT8, true); else SP_LAUNCH(SM_F32, SM_SIGN_INT8, false);
+        }
+      }
+#undef SP_LAUNCH
+    }
+    SM_HIP(ctx, hipGetLastError());
+    done += g;
+  }
+  return SM_OK;
+}
+
 int sm_launch_sign_pack(signmuon_ctx* ctx, const void* u, int dtype, int batch, int rows, int cols, int ld,
                         long long batch_stride, int fmt, void* out, long long out_stride_bytes) {
-  const long long n = (long long)rows * cols;
-  const long long bytes_per_row = (fmt == SM_SIGN_1BIT) ? 8 * ((n + 63) / 64) : (n + 7) / 8;  // threads per row
-  // the fast path reads whole 8-entry groups with 16-byte loads
-  const bool fast_ok = (ld == cols || (cols % 8 == 0 && ld % 8 == 0)) && sm_aligned(u, 16) &&
-                       (batch_stride % 8 == 0) &&
-                       (fmt == SM_SIGN_1BIT || (sm_aligned(out, 8) && out_stride_bytes % 8 == 0));
-  const unsigned gx = (unsigned)((bytes_per_row + TPB * 4 - 1) / (TPB * 4));
-  dim3 grid(gx, batch);
-  sm_launch_scope sc(ctx, SM_K_SIGN_PACK);
-#define SP_LAUNCH(DT, FMT, FAST)                                                                               \
-  hipLaunchKernelGGL((sm_sign_pack_kernel<DT, FMT, FAST>), grid, dim3(TPB), 0, ctx->stream, u, n, cols, ld,     \
-                     batch_stride, out, out_stride_bytes, bytes_per_row)
-  if (dtype == SM_BF16) {
-    if (fmt == SM_SIGN_1BIT) {
-      if (fast_ok) SP_LAUNCH(SM_BF16, SM_SIGN_1BIT, true); else SP_LAUNCH(SM_BF16, SM_SIGN_1BIT, false);
-    } else {
-      if (fast_ok) SP_LAUNCH(SM_BF16, SM_SIGN_INT8, true); else SP_LAUNCH(SM_BF16, SM_SIGN_INT8, false);
-    }
-  } else {
-    if (fmt == SM_SIGN_1BIT) {
-      if (fast_ok) SP_LAUNCH(SM_F32, SM_SIGN_1BIT, true); else SP_LAUNCH(SM_F32, SM_SIGN_1BIT, false);
-    } else {
-      if (fast_ok) SP_LAUNCH(SM_F32, SM_SIGN_INT8, true); else SP_LAUNCH(SM_F32, SM_SIGN_INT8, false);
-    }
-  }
-#undef SP_LAUNCH
-  SM_HIP(ctx, hipGetLastError());
-  return SM_OK;
+  sm_sp_desc D;
+  D.u = u;
+  D.out = out;
+  D.n = (long long)rows * cols;
+  D.batch_stride = batch_stride;
+  D.out_stride = out_stride_bytes;
+  D.bytes_per_row = 0;
+  D.cols = cols;
+  D.ld = ld;
+  D.blocks_per_row = 0;
+  D.block_begin = 0;
+  return sm_launch_sign_pack_group(ctx, &D, 1, dtype, fmt, batch);
 }
 
 int sm_launch_vote(signmuon_ctx* ctx, const sm_vote_args& v) {
@@ -525,7 +578,7 @@ int sm_launch_vote(signmuon_ctx* ctx, const sm_vote_args& v) {
     SM_HIP(ctx, hipGetLastError());
   }
   if (want_expand) {
-    vote_x_args a;
+    sm_vote_desc a;
     a.signs = v.signs;
     a.n = n;
     a.stride_bytes = v.stride_bytes;
@@ -537,24 +590,71 @@ int sm_launch_vote(signmuon_ctx* ctx, const sm_vote_args& v) {
     a.vfmt = v.vfmt;
     a.cols = v.cols;
     a.ld = v.ld;
-    const long long threads = (n + 3) / 4;
-    sm_launch_scope sc(ctx, SM_K_VOTE);
-    if (v.fmt == SM_SIGN_1BIT)
-      hipLaunchKernelGGL(sm_vote_expand_kernel<SM_SIGN_1BIT>, dim3((unsigned)((threads + TPB - 1) / TPB)), dim3(TPB), 0,
-                         ctx->stream, a);
-    else
-      hipLaunchKernelGGL(sm_vote_expand_kernel<SM_SIGN_INT8>, dim3((unsigned)((threads + TPB - 1) / TPB)), dim3(TPB), 0,
-                         ctx->stream, a);
+    a.block_begin = 0;
+    return sm_launch_vote_group(ctx, &a, 1, v.fmt);
+  }
+  return SM_OK;
+}
+
+int sm_launch_vote_group(signmuon_ctx* ctx, const sm_vote_desc* descs, int n, int fmt) {
+  int done = 0;
+  while (done < n) {
+    const int g = std::min(n - done, SM_VOTE_MAX_GROUP);
+    vote_g_args a;
+    a.n = g;
+    a.pad_ = 0;
+    long long blocks = 0;
+    for (int i = 0; i < g; ++i) {
+      a.d[i] = descs[done + i];
+      a.d[i].block_begin = (int)blocks;
+      blocks += (((a.d[i].n + 3) / 4) + TPB - 1) / TPB;
+    }
+    if (blocks > 0x7FFFFFFFLL) return sm_fail(ctx, SM_EUNSUPPORTED, "vote: too many entries for one launch");
+    if (blocks > 0) {
+      sm_launch_scope sc(ctx, SM_K_VOTE);
+      if (fmt == SM_SIGN_1BIT)
+        hipLaunchKernelGGL(sm_vote_expand_kernel<SM_SIGN_1BIT>, dim3((unsigned)blocks), dim3(TPB), 0, ctx->stream, a);
+      else
+        hipLaunchKernelGGL(sm_vote_expand_kernel<SM_SIGN_INT8>, dim3((unsigned)blocks), dim3(TPB), 0, ctx->stream, a);
+    }
     SM_HIP(ctx, hipGetLastError());
+    done += g;
+  }
+  return SM_OK;
+}
+
+int sm_launch_update_group(signmuon_ctx* ctx, const sm_upd_desc* descs, int n) {
+  int done = 0;
+  while (done < n) {
+    const int g = std::min(n - done, SM_UPD_MAX_GROUP);
+    upd_args a;
+    a.n = g;
+    a.pad_ = 0;
+    long long blocks = 0;
+    for (int i = 0; i < g; ++i) {
+      a.d[i] = descs[done + i];
+      a.d[i].block_begin = (int)blocks;
+      blocks += ((((long long)a.d[i].rows * a.d[i].cols + 3) / 4) + TPB - 1) / TPB;
+    }
+    if (blocks > 0) {
+      sm_launch_scope sc(ctx, SM_K_UPDATE);
+      hipLaunchKernelGGL(sm_update_kernel, dim3((unsigned)blocks), dim3(TPB), 0, ctx->stream, a);
+    }
+    SM_HIP(ctx, hipGetLastError());
+    done += g;
   }
   return SM_OK;
 }
 
 int sm_launch_update(signmuon_ctx* ctx, float* w, const bf16_t* d, int rows, int cols, int ld, float step) {
-  const long long threads = ((long long)rows * cols + 3) / 4;
-  sm_launch_scope sc(ctx, SM_K_UPDATE);
-  hipLaunchKernelGGL(sm_update_kernel, dim3((unsigned)((threads + TPB - 1) / TPB)), dim3(TPB), 0, ctx->stream, w, d,
-                     rows, cols, ld, step);
-  SM_HIP(ctx, hipGetLastError());
-  return SM_OK;
+  sm_upd_desc D;
+  D.w = w;
+  D.d = d;
+  D.rows = rows;
+  D.cols = cols;
+  D.ld = ld;
+  D.step = step;
+  D.block_begin = 0;
+  D.pad_ = 0;
+  return sm_launch_update_group(ctx, &D, 1);
 }
