@@ -1,0 +1,195 @@
+"""GPU parity at the benchmark's full sizes and launch configuration, plus edge shapes.
+
+The nanoGPT-124M-shaped step is run exactly as bench.py runs it (same StepPlan, grouped launches,
+256 x 256 GEMM tiles), with every intermediate tapped.  Bit-exact stages are checked on ALL blocks and
+workers; Newton-Schulz outputs are checked against the float32 oracle on one (block, worker) per
+distinct shape, and by properties that hold at any size on the rest.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import signmuon_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2605_16311_amd as pkg
+    return pkg
+
+
+def rel_and_agree(got, ref):
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    rel = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
+    big = np.abs(ref) > 1e-3 * np.max(np.abs(ref))
+    return rel, float(np.mean((got[big] >= 0) == (ref[big] >= 0)))
+
+
+def full_step_check(P, name, ns_blocks):
+    import bench
+    cfg, w, mom, grad = bench.make_inputs(name, torch, torch.device("cuda:0"))
+    shapes, M = cfg["shapes"], cfg["M"]
+    K, Kp, fmt = cfg["ns_steps"], cfg["local_polar_steps"], cfg["sign_fmt"]
+    lr, beta = 1e-3, 0.9
+    W0 = [t.cpu().numpy() for t in w]
+    G = [t.cpu().numpy() for t in grad]
+    # one warm step so the momentum is not the trivial (1 - beta) G
+    ctx = P.Context()
+    plan0 = P.StepPlan(w, mom, grad, beta=beta, lr=lr, ns_steps=K, sign_fmt=fmt, local_polar_steps=Kp)
+    P.signmuon_step(ctx, plan0)
+    torch.cuda.synchronize()
+    M1 = [t.cpu().numpy() for t in mom]
+    W1 = [t.cpu().numpy() for t in w]
+    d = [r * c for r, c in shapes]
+    stride = [O.packed_stride_bytes(x) if fmt == "1bit" else x for x in d]
+    signs = [torch.zeros((M, s), dtype=torch.uint8, device="cuda") for s in stride]
+    counts = [torch.zeros((x,), dtype=torch.int32, device="cuda") for x in d]
+    u_out = [torch.zeros((M, r, c), dtype=torch.bfloat16, device="cuda") for r, c in shapes]
+    d_out = [torch.zeros((r, c), dtype=torch.bfloat16, device="cuda") for r, c in shapes]
+    plan = P.StepPlan(w, mom, grad, beta=beta, lr=lr, ns_steps=K, sign_fmt=fmt, local_polar_steps=Kp,
+                      signs_out=signs, counts_out=counts, u_out=u_out, d_out=d_out)
+    P.signmuon_step(ctx, plan)
+    torch.cuda.synchronize()
+    for i, (r, c) in enumerate(shapes):
+        m_ref = O.momentum_update(M1[i], G[i], None, beta, 0.0, dtype=np.float32)
+        assert np.array_equal(mom[i].cpu().numpy().view(np.uint32), m_ref.view(np.uint32)), f"momentum block {i}"
+        U = u_out[i].float().cpu().numpy()
+        assert np.isfinite(U).all()
+        # properties that hold at any size: after 5 cubic steps from a Frobenius-scaled start the
+        # spectrum lies in (0, 1]; so ||U||_F^2 <= min(r, c) and ||U||_op <= 1 (checked by power bound)
+        fro2 = np.sum(U.astype(np.float64) ** 2, axis=(1, 2))
+        assert np.all(fro2 <= min(r, c) * 1.02), f"block {i}: ||U||_F^2 {fro2.max()} > rank bound"
+        if i in ns_blocks:
+            for p in (0, M - 1):
+                ref = O.polar_ns(m_ref[p], K, dtype=np.float32)
+                rel, agree = rel_and_agree(U[p], ref)
+                assert rel <= 2e-2 and agree >= 0.999, f"U block {i} worker {p}: rel {rel:.3e} agree {agree:.5f}"
+        if fmt == "1bit":
+            s_ref = np.stack([O.pack_bits(O.sign_entries(U[p])) for p in range(M)])
+            vote_ref, c_ref = O.majority_vote_bits(s_ref, M, d[i])
+        else:
+            s_ref = np.stack([O.signs_pm1(U[p]).reshape(-1) for p in range(M)])
+            vote_ref, c_ref = O.majority_vote_int8(s_ref)
+            s_ref = s_ref.view(np.uint8)
+        assert np.array_equal(signs[i].cpu().numpy(), s_ref), f"signs block {i}"
+        assert np.array_equal(counts[i].cpu().numpy(), c_ref), f"counts block {i}"
+        D = d_out[i].float().cpu().numpy()
+        S_bar = vote_ref.reshape(r, c)
+        if Kp == 0:
+            assert np.array_equal(D, S_bar.astype(np.float32))
+        else:
+            assert np.sum(D.astype(np.float64) ** 2) <= min(r, c) * 1.02
+            if i in ns_blocks:
+                ref = O.local_polar(S_bar, Kp, dtype=np.float32)
+                rel, agree = rel_and_agree(D, ref)
+                assert rel <= 2e-2 and agree >= 0.999, f"D block {i}: rel {rel:.3e} agree {agree:.5f}"
+        w_ref = O.apply_update(W1[i], D, lr, False, dtype=np.float32)
+        assert np.array_equal(w[i].cpu().numpy().view(np.uint32), w_ref.view(np.uint32)), f"W block {i}"
+    ctx.close()
+    del W0
+
+
+def test_nanogpt124m_step_in_bench_configuration(P):
+    # one block of every distinct shape gets the full Newton-Schulz comparison
+    full_step_check(P, "nanogpt124m", ns_blocks={0, 1, 2, 3, 47})
+
+
+def test_resnet50_step_in_bench_configuration(P):
+    full_step_check(P, "resnet50", ns_blocks={0, 1, 2, 3, 4, 5})
+
+
+def test_int8_vote_path_m16_with_ties(P):
+    """The int8 transport at M = 16 (iid workers: about a fifth of the entries tie), with a local polar step."""
+    shapes, M = [(256, 1024), (1024, 256), (192, 320)], 16
+    ctx = P.Context()
+    W0 = [wl.weights(r, c, block=i, stream=41) for i, (r, c) in enumerate(shapes)]
+    G = [wl.normal((M, r, c), stream=41, block=i) for i, (r, c) in enumerate(shapes)]
+    w = [torch.from_numpy(a).cuda() for a in W0]
+    mom = [torch.zeros((M, r, c), device="cuda") for r, c in shapes]
+    grad = [torch.from_numpy(a).cuda() for a in G]
+    d = [r * c for r, c in shapes]
+    signs = [torch.zeros((M, x), dtype=torch.int8, device="cuda") for x in d]
+    counts = [torch.zeros((x,), dtype=torch.int32, device="cuda") for x in d]
+    u_out = [torch.zeros((M, r, c), dtype=torch.bfloat16, device="cuda") for r, c in shapes]
+    d_out = [torch.zeros((r, c), dtype=torch.bfloat16, device="cuda") for r, c in shapes]
+    plan = P.StepPlan(w, mom, grad, beta=0.9, lr=1e-2, ns_steps=5, sign_fmt="int8", local_polar_steps=5,
+                      signs_out=signs, counts_out=counts, u_out=u_out, d_out=d_out)
+    P.signmuon_step(ctx, plan)
+    torch.cuda.synchronize()
+    ties = 0
+    for i, (r, c) in enumerate(shapes):
+        U = u_out[i].float().cpu().numpy()
+        s_ref = np.stack([O.signs_pm1(U[p]).reshape(-1) for p in range(M)])
+        vote_ref, tot = O.majority_vote_int8(s_ref)
+        ties += int(np.sum(tot == 0))
+        assert np.array_equal(signs[i].cpu().numpy(), s_ref)
+        assert np.array_equal(counts[i].cpu().numpy(), tot)
+        D = d_out[i].float().cpu().numpy()
+        ref = O.local_polar(vote_ref.reshape(r, c), 5, dtype=np.float32)
+        rel, agree = rel_and_agree(D, ref)
+        assert rel <= 2e-2 and agree >= 0.999
+        w_ref = O.apply_update(W0[i], D, 1e-2, False, dtype=np.float32)
+        assert np.array_equal(w[i].cpu().numpy(), w_ref)
+    assert ties > 0.1 * sum(d)          # the tie rule really was exercised
+    ctx.close()
+
+
+def test_vector_shaped_and_tiny_blocks(P):
+    """Blocks with one dimension equal to 1 (vector parameters treated as m x 1) and a 1 x 1 block."""
+    shapes, M = [(1, 96), (96, 1), (1, 1), (3, 5)], 3
+    ctx = P.Context()
+    W0 = [wl.weights(r, c, block=i, stream=42) for i, (r, c) in enumerate(shapes)]
+    G = [wl.normal((M, r, c), stream=42, block=i) for i, (r, c) in enumerate(shapes)]
+    w = [torch.from_numpy(a).cuda() for a in W0]
+    mom = [torch.zeros((M, r, c), device="cuda") for r, c in shapes]
+    grad = [torch.from_numpy(a).cuda() for a in G]
+    u_out = [torch.zeros((M, r, c), dtype=torch.bfloat16, device="cuda") for r, c in shapes]
+    counts = [torch.zeros((r * c,), dtype=torch.int32, device="cuda") for r, c in shapes]
+    plan = P.StepPlan(w, mom, grad, beta=0.9, lr=0.5, ns_steps=5, u_out=u_out, counts_out=counts)
+    P.signmuon_step(ctx, plan)
+    torch.cuda.synchronize()
+    for i, (r, c) in enumerate(shapes):
+        m_ref = O.momentum_update(np.zeros_like(G[i]), G[i], None, 0.9, dtype=np.float32)
+        U = u_out[i].float().cpu().numpy()
+        for p in range(M):
+            ref = O.polar_ns(m_ref[p], 5, dtype=np.float32)
+            rel, agree = rel_and_agree(U[p], ref)
+            assert rel <= 2e-2 and agree >= 0.999, (i, p, rel, agree)
+        s_ref = np.stack([O.pack_bits(O.sign_entries(U[p])) for p in range(M)])
+        vote, c_ref = O.majority_vote_bits(s_ref, M, r * c)
+        assert np.array_equal(counts[i].cpu().numpy(), c_ref)
+        assert np.array_equal(w[i].cpu().numpy(), O.apply_update(W0[i], vote.reshape(r, c), 0.5, dtype=np.float32))
+    ctx.close()
+
+
+def test_many_blocks_exceed_one_descriptor_table(P):
+    """More blocks than fit one grouped launch (tables hold 40-48 blocks) and more than 32 distinct shapes."""
+    shapes = [(64 + 8 * (i % 40), 64) for i in range(70)]
+    M = 2
+    ctx = P.Context()
+    W0 = [wl.weights(r, c, block=i, stream=43) for i, (r, c) in enumerate(shapes)]
+    G = [wl.normal((M, r, c), stream=43, block=i) for i, (r, c) in enumerate(shapes)]
+    w = [torch.from_numpy(a).cuda() for a in W0]
+    mom = [torch.zeros((M, r, c), device="cuda") for r, c in shapes]
+    grad = [torch.from_numpy(a).cuda() for a in G]
+    u_out = [torch.zeros((M, r, c), dtype=torch.bfloat16, device="cuda") for r, c in shapes]
+    d_out = [torch.zeros((r, c), dtype=torch.bfloat16, device="cuda") for r, c in shapes]
+    plan = P.StepPlan(w, mom, grad, beta=0.9, lr=0.1, ns_steps=3, local_polar_steps=2, u_out=u_out, d_out=d_out)
+    P.signmuon_step(ctx, plan)
+    torch.cuda.synchronize()
+    for i, (r, c) in enumerate(shapes):
+        m_ref = O.momentum_update(np.zeros_like(G[i]), G[i], None, 0.9, dtype=np.float32)
+        assert np.array_equal(mom[i].cpu().numpy(), m_ref)
+        U = u_out[i].float().cpu().numpy()
+        ref = O.polar_ns(m_ref[1], 3, dtype=np.float32)
+        rel, agree = rel_and_agree(U[1], ref)
+        assert rel <= 2e-2 and agree >= 0.999, (i, rel, agree)
+        vote = np.where(np.sum(np.where(U >= 0, 1, -1), axis=0) >= 0, 1, -1)
+        D = d_out[i].float().cpu().numpy()
+        rel, agree = rel_and_agree(D, O.local_polar(vote, 2, dtype=np.float32))
+        assert rel <= 2e-2 and agree >= 0.999, (i, rel, agree)
+        assert np.array_equal(w[i].cpu().numpy(), O.apply_update(W0[i], D, 0.1, dtype=np.float32))
+    ctx.close()
