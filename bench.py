@@ -233,7 +233,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "M": main_res["M"], "blocks": main_res["n_blocks"],
                    "entries": main_res["entries"], "ns_steps": 5, "scale": "fro"},
-        "roofline": {"kernel": "sm_ns_gemm_pipe_kernel<1, 256> (apply half-step)", "bound": "mfma", "achieved": ach,
+        "roofline": {"kernel": "sm_ns_gemm_kernel<1, 256> (apply half-step)", "bound": "mfma", "achieved": ach,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": (ach / MFMA_BF16_PEAK_TFLOPS) if ach else None, "traffic": traffic,
                      "avg_launch_ms": main_res["ns_apply"]["avg_ms"],

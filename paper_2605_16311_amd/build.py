@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsignmuon.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-SOURCES = ["ctx.hip", "stream.hip", "layout.hip", "poweriter.hip", "ns_gemm.hip", "ns_gemm_v1.hip", "api.hip"]
+SOURCES = ["ctx.hip", "stream.hip", "layout.hip", "poweriter.hip", "ns_gemm.hip", "api.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]

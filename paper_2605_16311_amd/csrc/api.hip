@@ -202,7 +202,7 @@ int run_ns(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coe
             }
           }
         }
-        int rc = sm_launch_gemm_pipe(ctx, ga, phase == 0 ? SM_K_NS_GRAM : SM_K_NS_APPLY);
+        int rc = sm_launch_gemm(ctx, ga, phase == 0 ? SM_K_NS_GRAM : SM_K_NS_APPLY);
         if (rc != SM_OK) return rc;
         if (phase == 0 && c != 0.f) {  // Bm = c A A^T + b A + a I   (A symmetric)
           ga.scale_pow = 0;
@@ -220,7 +220,7 @@ int run_ns(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coe
             P.lda = P.ldb = P.ldc = cl.s;
             P.layout = 0;
           }
-          rc = sm_launch_gemm_pipe(ctx, ga, SM_K_NS_GRAM);
+          rc = sm_launch_gemm(ctx, ga, SM_K_NS_GRAM);
           if (rc != SM_OK) return rc;
         }
       }

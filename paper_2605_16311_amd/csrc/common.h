@@ -155,17 +155,14 @@ int sm_launch_copy_in(signmuon_ctx* ctx, const void* src, int dtype, int batch, 
 // dst[b][rows][cols] (f32 or bf16) <- scale[b] * src[b][rows][ld]; scale may be null
 int sm_launch_copy_out(signmuon_ctx* ctx, const bf16_t* src, int ld, long long src_stride, int batch, int rows,
                        int cols, void* dst, int dtype, const float* scale);
-// dst[b][C][ldd] <- transpose(src[b][R][lds]) for bf16, R and C multiples of 64
-int sm_launch_transpose(signmuon_ctx* ctx, const bf16_t* src, int R, int C, int lds, long long sstride,
-                        bf16_t* dst, int ldd, long long dstride, int batch);
 // sumsq[b] = sum of squares of x[b][0..n) (f32 or bf16; two stages, fixed order);
 // scratch: batch * ceil(n / SM_MOM_CHUNK) floats
 int sm_launch_sumsq(signmuon_ctx* ctx, const void* x, int dtype, long long n_per_batch, int batch, float* scratch,
                     float* sumsq);
 
 // ---------------------------------------------------------------- GEMM (ns_gemm.hip)
-// C[b] = alpha * scale[b]^scale_pow * (A[b] * B[b]^T) + gamma * R[b] + diag * I
-// A: [M][lda], B: [N][ldb] (both K-contiguous), C, R: [M][ldc]; M, N, K multiples of 64.
+// C[b] = alpha * scale[b]^scale_pow * (opA[b] * opB[b]^T) + gamma * R[b] + diag * I
+// opA is M x K, opB is N x K, C and R are [M][ldc]; M, N, K multiples of 64.
 struct sm_gemm_prob {
   const bf16_t* A;
   const bf16_t* B;
@@ -176,9 +173,9 @@ struct sm_gemm_prob {
   int M, N, K;
   int lda, ldb, ldc;
   int batch;
-  int tiles_m, tiles_n;
-  int tile_begin;
-  int layout;            // pipelined kernel only; bit 0: A stored [K][M], bit 1: B stored [K][N]
+  int tiles_m, tiles_n;  // filled by the launcher
+  int tile_begin;        // filled by the launcher
+  int layout;            // bit 0: A stored [K][M] (lda = its row length), bit 1: B stored [K][N]
 };
 constexpr int SM_GEMM_MAX_PROB = 32;
 struct sm_gemm_args {
@@ -190,14 +187,9 @@ struct sm_gemm_args {
   int pad_;
   sm_gemm_prob p[SM_GEMM_MAX_PROB];
 };
-// Fills tiles_m/tiles_n/tile_begin/total_tiles and launches; klass is SM_K_NS_GRAM or SM_K_NS_APPLY.
-// Register-staged kernel, both operands K-contiguous (kept as the reference implementation).
-int sm_launch_gemm_nt(signmuon_ctx* ctx, sm_gemm_args& args, int klass);
-// Pipelined kernel.  Per problem, layout bit 0: A is stored [K][M]; bit 1: B is stored [K][N]
-// (lda/ldb are then the row lengths of those arrays).  SM_K_NS_GRAM: A == B, layout 0 or 3, only
-// the upper triangle of tiles is computed and mirrored.  SM_K_NS_APPLY: layout 0 or 2.
-// K must be a multiple of 32.
-int sm_launch_gemm_pipe(signmuon_ctx* ctx, sm_gemm_args& args, int klass);
+// One grouped launch over the problem table.  klass SM_K_NS_GRAM: A == B, layout 0 or 3, symmetric
+// output (upper triangle of tiles computed, mirrored).  klass SM_K_NS_APPLY: layout 0 or 2.
+int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, int klass);
 
 // ---------------------------------------------------------------- power iteration (poweriter.hip)
 // sigma[b] = PowerIter(X[b], P, eps, v0[b]); X bf16 [rows][ld]; scratch: (rows + 2*cols + 4) floats per batch

@@ -138,8 +138,8 @@ int signmuon_profile_read(signmuon_ctx* ctx, int kernel_class, int64_t* launches
 const char* signmuon_kernel_name(int k) {
   switch (k) {
     case SM_K_MOMENTUM: return "sm_momentum_kernel";
-    case SM_K_NS_GRAM: return "sm_ns_gemm_kernel(gram)";
-    case SM_K_NS_APPLY: return "sm_ns_gemm_kernel(apply)";
+    case SM_K_NS_GRAM: return "sm_ns_gemm_kernel<0,*> (Gram)";
+    case SM_K_NS_APPLY: return "sm_ns_gemm_kernel<1,*> (apply)";
     case SM_K_SIGN_PACK: return "sm_sign_pack_kernel";
     case SM_K_VOTE: return "sm_vote_kernel";
     case SM_K_UPDATE: return "sm_update_kernel";

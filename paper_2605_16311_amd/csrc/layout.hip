@@ -1,6 +1,6 @@
 // Layout helpers around the Newton-Schulz workspace: copies between caller
-// matrices and the zero-padded bf16 working layout, bf16 transposes, and sums
-// of squares for the Frobenius scale of Alg. PolarNS.
+// matrices and the zero-padded bf16 working layout, and sums of squares for
+// the Frobenius scale of Alg. PolarNS.
 #include "common.h"
 
 namespace {
@@ -38,39 +38,6 @@ __global__ void __launch_bounds__(TPB) sm_copy_out_kernel(const bf16_t* __restri
     reinterpret_cast<float*>(dst)[(long long)b * n + e] = v;
   else
     reinterpret_cast<bf16_t*>(dst)[(long long)b * n + e] = (bf16_t)v;
-}
-
-// 64 x 64 bf16 tile transpose through LDS.  grid = (C/64, R/64, batch).
-__global__ void __launch_bounds__(TPB) sm_transpose_kernel(const bf16_t* __restrict__ src, int lds_, long long sstride,
-                                                           bf16_t* __restrict__ dst, int ldd, long long dstride) {
-  __shared__ unsigned short tile[64][66];
-  const int b = blockIdx.z;
-  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-  const unsigned short* s = reinterpret_cast<const unsigned short*>(src) + (long long)b * sstride;
-  unsigned short* d = reinterpret_cast<unsigned short*>(dst) + (long long)b * dstride;
-  const int t = threadIdx.x;
-#pragma unroll
-  for (int pass = 0; pass < 2; ++pass) {
-    const int r = (t >> 3) + 32 * pass, ch = t & 7;
-    const u32x4 v = *reinterpret_cast<const u32x4*>(s + (long long)(r0 + r) * lds_ + c0 + ch * 8);
-    const unsigned wv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      tile[r][ch * 8 + 2 * k] = (unsigned short)(wv[k] & 0xFFFFu);
-      tile[r][ch * 8 + 2 * k + 1] = (unsigned short)(wv[k] >> 16);
-    }
-  }
-  __syncthreads();
-#pragma unroll
-  for (int pass = 0; pass < 2; ++pass) {
-    const int c = (t >> 3) + 32 * pass, ch = t & 7;  // output row c, output cols ch*8..+7
-    unsigned wv[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-      wv[k] = (unsigned)tile[ch * 8 + 2 * k][c] | ((unsigned)tile[ch * 8 + 2 * k + 1][c] << 16);
-    u32x4 v = {wv[0], wv[1], wv[2], wv[3]};
-    *reinterpret_cast<u32x4*>(d + (long long)(c0 + c) * ldd + r0 + ch * 8) = v;
-  }
 }
 
 template <int DT>
@@ -124,24 +91,6 @@ int sm_launch_copy_out(signmuon_ctx* ctx, const bf16_t* src, int ld, long long s
     hipLaunchKernelGGL(sm_copy_out_kernel<SM_BF16>, grid, dim3(TPB), 0, ctx->stream, src, ld, src_stride, rows, cols,
                        dst, scale);
   SM_HIP(ctx, hipGetLastError());
-  return SM_OK;
-}
-
-int sm_launch_transpose(signmuon_ctx* ctx, const bf16_t* src, int R, int C, int lds, long long sstride, bf16_t* dst,
-                        int ldd, long long dstride, int batch) {
-  if (R % 64 || C % 64 || lds % 8 || ldd % 8 || !sm_aligned(src, 16) || !sm_aligned(dst, 16) || sstride % 8 ||
-      dstride % 8)
-    return sm_fail(ctx, SM_EINVAL, "internal: transpose operand not padded/aligned");
-  int done = 0;
-  while (done < batch) {  // grid.z is limited to 65535
-    const int g = std::min(batch - done, 32768);
-    dim3 grid(C / 64, R / 64, g);
-    sm_launch_scope sc(ctx, SM_K_OTHER);
-    hipLaunchKernelGGL(sm_transpose_kernel, grid, dim3(TPB), 0, ctx->stream, src + (long long)done * sstride, lds,
-                       sstride, dst + (long long)done * dstride, ldd, dstride);
-    SM_HIP(ctx, hipGetLastError());
-    done += g;
-  }
   return SM_OK;
 }
 

@@ -1,92 +1,173 @@
-// Newton-Schulz GEMMs of Alg. PolarNS on the gfx950 matrix cores.
+// Newton-Schulz GEMMs of Alg. PolarNS on the gfx950 matrix cores: pipelined kernel, K slices of 64.
 //
-// One grouped launch computes, for every problem in a table and every batch
-// item,   C = alpha * scale^pow * (A * B^T) + gamma * R + diag * I
-// with A [M][K] and B [N][K] both K-contiguous bf16, fp32 accumulation in
-// v_mfma_f32_32x32x16_bf16.  The Gram step of the iteration (A = B = Y, output
-// a I + b Y Y^T) and the polynomial apply step are both of this form.
+//   C = alpha * scale^pow * (opA * opB^T) + gamma * R + diag * I      (bf16 in, fp32 accumulate)
 //
-// Tiling: a workgroup of 4 waves owns a BM x BN tile of C; K is walked in
-// slices of 64.  Slices are staged in LDS (double buffered) as rows of 128
-// bytes = 8 chunks of 16 bytes; chunk c of row r sits at chunk position
-// c ^ ((r >> 1) & 7), which makes the 16 rows that one ds_read_b128 phase
-// touches fall in distinct banks.  Each wave owns a WM x WN sub-tile as
-// (WM/32) x (WN/32) MFMA tiles.  The MFMA is issued with the B fragment as the
-// first operand, so a lane ends up holding one row m and 4 consecutive columns
-// n of C: the epilogue writes those 8-byte groups to LDS and the tile leaves
-// with 16-byte coalesced row stores.
+// opA is an M x K operand and opB an N x K operand; each may be stored K-contiguous
+// ([rows][K], "KC") or MN-contiguous ([K][rows], "MN").  The four half-steps of the iteration are
+//   Gram,  rows <= cols : A = B = Y           (KC, KC)   symmetric output
+//   Gram,  rows >  cols : A = B = Y           (MN, MN)   symmetric output
+//   apply, rows <= cols : A = Bm, B = Y       (KC, MN)   Y' = Bm Y
+//   apply, rows >  cols : A = Y,  B = Bm      (KC, KC)   Y' = Y Bm   (Bm symmetric)
+// so Y is only ever read in its own row-major layout and no transposed copy exists.  The
+// layout is a per-problem flag: one launch covers every matrix of a half-step.
 //
-// Workgroup ids are dealt round-robin to the 8 XCDs by the hardware; the kernel
-// renumbers them so that each XCD walks one contiguous eighth of the tile list
-// and neighbouring tiles (sharing operand panels) hit the same L2.
+// Structure.  A workgroup of 8 waves (2 per SIMD) owns a TS x TS tile of C (TS = 256, or 128
+// for launches with little work); each wave a (TS/2) x (TS/4) sub-tile held as accumulators of
+// v_mfma_f32_32x32x16_bf16.  K advances in slices of 64 (four MFMA k-steps), so that every
+// global->LDS request covers a whole 128-byte line of a K-contiguous operand: the per-CU
+// L2 -> LDS path is limited by the number of outstanding requests, not by bytes.
+// Two LDS stages.  Timeline of slice j (stage j & 1):
+//     barrier B(j-1)
+//     issue slice j+1 -> other stage          (free: every wave finished reading slice j-1)
+//     fetch k-step 0 of slice j               (visible since B(j-1))
+//     MFMA  k-step 3 of slice j-1             (fragments were read before B(j-1))
+//     fetch 1, MFMA 0; fetch 2, MFMA 1; fetch 3, MFMA 2
+//     wait: own LDS reads done, own loads of slice j+1 landed;  barrier B(j)
+// The barrier sits between two MFMA batches, so the matrix pipe keeps working while waves wait
+// for each other, and there is one barrier per 64 of K.  Each stage is its own __shared__
+// array so the compiler's tracking of pending global->LDS writes does not stall the LDS reads
+// of the other stage; buffer loads (not flat/global) keep the lgkmcnt waits exact.
+//
+// LDS layouts (TS * 128 bytes per operand slice).  The LDS serves a 16-byte read sixteen lanes
+// at a time, one 16-byte bank group per lane, and an 8-byte read thirty-two lanes at a time:
+//   KC: TS rows of 128 bytes; chunk c of row r sits at slot c ^ ((r >> 1) & 7); fragments are
+//       read with ds_read_b128.
+//   MN: 64 k-rows of 2 TS bytes; 16-byte chunk c of k-row k sits at slot c ^ (4 (k & 3));
+//       fragments are read with ds_read_b64_tr_b16, which hands lane i of a 16-lane group
+//       column i of the 4 x 16 block whose rows the group's lanes address.
+// The global->LDS load writes its 64 lanes in order, so each lane fetches the chunk that
+// belongs in its slot.
+//
+// Symmetric outputs: only tiles with tile_m <= tile_n are computed; off-diagonal tiles are
+// also stored mirrored.
 #include "common.h"
 
-namespace {
+namespace sm_gemm {
 
-constexpr int BK = 64;
-constexpr int NTHREADS = 256;
+constexpr int BK = 64, NTH = 512;
 
-__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
-template <int BM, int BN, int WM, int WN, int KIND>
-__global__ void __launch_bounds__(NTHREADS) sm_ns_gemm_nt_kernel(const sm_gemm_args args) {
-  constexpr int WGM = BM / WM;            // waves along m
-  constexpr int FM = WM / 32, FN = WN / 32;
-  constexpr int LA = BM / 32, LB = BN / 32;  // 16-byte chunks per thread per slice
-  static_assert((BM / WM) * (BN / WN) == 4, "4 waves");
-  constexpr int CS = BN + 4;              // epilogue row stride in elements (BN*2 + 8 bytes)
+__device__ __forceinline__ const bf16_t* uniform_ptr(const bf16_t* p) {
+  const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+  const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return reinterpret_cast<const bf16_t*>(((unsigned long long)hi << 32) | lo);
+}
 
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16_t* As = reinterpret_cast<bf16_t*>(smem);                  // [2][BM][64]
-  bf16_t* Bs = As + 2 * BM * BK;                                 // [2][BN][64]
+// Per-lane constants of one operand: where its global->LDS loads read, where its fragments sit.
+template <bool MN, int TS>
+struct operand_lane {
+  static constexpr int NLOAD = TS / 64;  // wave-loads of this operand per wave and slice
+  static constexpr int ROWB = TS * 2;    // MN: bytes per k-row
+  int voff[NLOAD];  // byte offset of this lane's wave-loads inside the operand (slice offset is scalar)
+  int frag_off;     // KC: LDS byte offset of this lane's row in fragment 0
+  int frag_mn[4];   // MN: LDS byte offset of fragment f (k-step 0, first half) for this lane
+  int ks_off[4];    // offset of k-step 0..3 inside the slice
+  int kstep;        // scalar byte step per K slice
 
-  // ---- which tile
-  const int wg = blockIdx.x;
-  const int L = (wg & 7) * args.tiles_per_xcd + (wg >> 3);
-  if (L >= args.total_tiles) return;
-  int pi = 0;
-  while (pi + 1 < args.n_prob && L >= args.p[pi + 1].tile_begin) ++pi;
-  const sm_gemm_prob& P = args.p[pi];
-  int t = L - P.tile_begin;
-  const int per_batch = P.tiles_m * P.tiles_n;
-  const int b = t / per_batch;
-  t -= b * per_batch;
-  const int tn = t / P.tiles_m, tm = t - tn * P.tiles_m;
-  const int m0 = tm * BM, n0 = tn * BN;
+  // row0: first tile row of the workgroup; wrow: first row of this wave's sub-tile inside the tile
+  __device__ __forceinline__ void init(int lane, int wv, int row0, int rows, int ld, int wrow) {
+    if (!MN) {
+#pragma unroll
+      for (int q = 0; q < NLOAD; ++q) {
+        const int row = 8 * (NLOAD * wv + q) + (lane >> 3);
+        const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+        voff[q] = (min(row0 + row, rows - 1) * ld + chunk * 8) * 2;
+      }
+      const int fr = lane & 31, fg = lane >> 5, fsw = (fr >> 1) & 7;  // same swizzle for rows fr + 32 f
+      frag_off = (wrow + fr) * (BK * 2);
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) ks_off[ks] = ((2 * ks + fg) ^ fsw) * 16;
+      kstep = BK * 2;
+    } else {
+      constexpr int LPR = ROWB / 16;  // lanes (16-byte chunks) per k-row
+      constexpr int KPL = 64 / LPR;   // k-rows per wave-load
+#pragma unroll
+      for (int q = 0; q < NLOAD; ++q) {
+        const int k = KPL * (NLOAD * wv + q) + lane / LPR;
+        const int chunk = (lane % LPR) ^ (4 * (k & 3));
+        voff[q] = (k * ld + min(row0 + chunk * 8, rows - 8)) * 2;
+      }
+      // transposed read: 16-lane group g16, lane i in it; the group covers columns 16 (g16 & 1) ..+15
+      // and k rows 8 (g16 >> 1) + 4 h + (i >> 2), h = 0, 1
+      const int i = lane & 15, g16 = lane >> 4;
+      const int col = wrow + 16 * (g16 & 1) + 4 * (i & 3);
+      const int k = 8 * (g16 >> 1) + (i >> 2);
+#pragma unroll
+      for (int f = 0; f < 4; ++f)  // fragment f lies 32 columns further
+        frag_mn[f] = k * ROWB + ((((col + 32 * f) >> 3) ^ (4 * (i >> 2))) << 4) + (col & 7) * 2;
+      frag_off = 0;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) ks_off[ks] = 16 * ks * ROWB;
+      kstep = BK * ld * 2;
+    }
+  }
+  // fragment f (32 rows further per f) of k-step ks from stage base s
+  __device__ __forceinline__ bf16x8 fetch(const unsigned char* s, int f, int ks) const {
+    if (!MN) {
+      return *reinterpret_cast<const bf16x8*>(s + frag_off + f * 32 * (BK * 2) + ks_off[ks]);
+    } else {
+      const unsigned char* p = s + frag_mn[f] + ks_off[ks];
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 4 * ROWB));
+      const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      return __builtin_bit_cast(bf16x8, v);
+    }
+  }
+};
+
+// One TS x TS tile of one problem.  The four stage arrays are the kernel's own __shared__
+// variables, passed by reference so that every access keeps its identity after inlining.
+template <int TS, bool A_MN, bool B_MN, bool SYM>
+__device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gemm_prob& P, int b, int tm, int tn,
+                                          unsigned char (&sA0)[TS * 128], unsigned char (&sA1)[TS * 128],
+                                          unsigned char (&sB0)[TS * 128], unsigned char (&sB1)[TS * 128]) {
+  constexpr int WM = TS / 2, WN = TS / 4, FM = TS / 64, FN = TS / 128, NLOAD = TS / 64;
+  const int m0 = tm * TS, n0 = tn * TS;
   const int M = P.M, N = P.N, K = P.K;
-  const bf16_t* __restrict__ A = P.A + (long long)b * P.sA;
-  const bf16_t* __restrict__ B = P.B + (long long)b * P.sB;
+  // the operand bases depend on the workgroup only: pin them to scalar registers so that the
+  // buffer descriptors are wave-uniform (no waterfall loop around the loads)
+  const bf16_t* __restrict__ A = uniform_ptr(P.A + (long long)b * P.sA);
+  const bf16_t* __restrict__ B = uniform_ptr(P.B + (long long)b * P.sB);
 
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int w_m = wv % WGM, w_n = wv / WGM;
+  // Opaque copy of the thread id: everything derived from it is recomputed per tile instead of
+  // being hoisted out of the persistent tile loop for both operand layouts at once (which
+  // would cost more registers than the kernel has).
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, wv = tid >> 6;
+  const int w_m = wv & 1, w_n = wv >> 1;
 
-  // ---- global -> register staging: thread covers chunk lp of rows lr + 32 j
-  const int lp = tid & 7, lr = tid >> 3;
-  const bf16_t* ga[LA];
-  const bf16_t* gb[LB];
+  // ---- global -> LDS: TS/8 wave-loads per operand slice; this wave issues NLOAD of A and of B.
+  // Buffer loads: the per-lane byte offset is fixed for the whole K walk, the slice offset is scalar.
+  const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A), 0, 0x7FFFFFFF, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(B), 0, 0x7FFFFFFF, 0x00020000);
+  operand_lane<A_MN, TS> oa;
+  operand_lane<B_MN, TS> ob;
+  oa.init(lane, wv, m0, M, P.lda, w_m * WM);
+  ob.init(lane, wv, n0, N, P.ldb, w_n * WN);
+  // plain locals: the buffer-load builtin is not instantiated on the host side when its
+  // operands are member expressions of a dependent type
+  int va[NLOAD], vb[NLOAD];
 #pragma unroll
-  for (int j = 0; j < LA; ++j) ga[j] = A + (long long)min(m0 + lr + 32 * j, M - 1) * P.lda + lp * 8;
-#pragma unroll
-  for (int j = 0; j < LB; ++j) gb[j] = B + (long long)min(n0 + lr + 32 * j, N - 1) * P.ldb + lp * 8;
-  u32x4 ra[LA], rb[LB];
-  auto load_slice = [&](int k0) {
-#pragma unroll
-    for (int j = 0; j < LA; ++j) ra[j] = *reinterpret_cast<const u32x4*>(ga[j] + k0);
-#pragma unroll
-    for (int j = 0; j < LB; ++j) rb[j] = *reinterpret_cast<const u32x4*>(gb[j] + k0);
-  };
-  auto store_slice = [&](int buf) {
-#pragma unroll
-    for (int j = 0; j < LA; ++j) {
-      const int r = lr + 32 * j;
-      *reinterpret_cast<u32x4*>(As + buf * BM * BK + r * BK + swz(r, lp) * 8) = ra[j];
-    }
-#pragma unroll
-    for (int j = 0; j < LB; ++j) {
-      const int r = lr + 32 * j;
-      *reinterpret_cast<u32x4*>(Bs + buf * BN * BK + r * BK + swz(r, lp) * 8) = rb[j];
-    }
-  };
+  for (int q = 0; q < NLOAD; ++q) {
+    va[q] = oa.voff[q];
+    vb[q] = ob.voff[q];
+  }
+  const int ksa = __builtin_amdgcn_readfirstlane(oa.kstep), ksb = __builtin_amdgcn_readfirstlane(ob.kstep);
+#define ISSUE(sa, sb, slice)                                                                                          \
+  {                                                                                                                   \
+    _Pragma("unroll") for (int q = 0; q < NLOAD; ++q) {                                                               \
+      const int voa = va[q], vob = vb[q];                                                                             \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, LDS_PTR((sa) + (NLOAD * wv + q) * 1024), 16, voa, (slice) * ksa,   \
+                                               0, 0);                                                                 \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, LDS_PTR((sb) + (NLOAD * wv + q) * 1024), 16, vob, (slice) * ksb,   \
+                                               0, 0);                                                                 \
+    }                                                                                                                 \
+  }
 
   f32x16 acc[FM][FN];
 #pragma unroll
@@ -96,40 +177,72 @@ __global__ void __launch_bounds__(NTHREADS) sm_ns_gemm_nt_kernel(const sm_gemm_a
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int fr = lane & 31, fg = lane >> 5;
-  const int nk = K / BK;
-  load_slice(0);
-  store_slice(0);
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) load_slice((kt + 1) * BK);
-    const bf16_t* as = As + buf * BM * BK;
-    const bf16_t* bs = Bs + buf * BN * BK;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 fa[FM], fb[FN];
-#pragma unroll
-      for (int i = 0; i < FM; ++i) {
-        const int r = w_m * WM + i * 32 + fr;
-        fa[i] = *reinterpret_cast<const bf16x8*>(as + r * BK + swz(r, 2 * ks + fg) * 8);
-      }
-#pragma unroll
-      for (int j = 0; j < FN; ++j) {
-        const int r = w_n * WN + j * 32 + fr;
-        fb[j] = *reinterpret_cast<const bf16x8*>(bs + r * BK + swz(r, 2 * ks + fg) * 8);
-      }
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) store_slice(buf ^ 1);
-    __syncthreads();
+  // two fragment sets: while the matrix pipe works through one, the LDS reads of the other are in flight
+  bf16x8 fa[2][FM], fb[2][FN];
+#define FETCH(set, sa, sb, ks)                                                          \
+  {                                                                                     \
+    _Pragma("unroll") for (int i = 0; i < FM; ++i) fa[set][i] = oa.fetch(sa, i, ks);    \
+    _Pragma("unroll") for (int j = 0; j < FN; ++j) fb[set][j] = ob.fetch(sb, j, ks);    \
+  }
+#define MMA(set)                                                                                                \
+  {                                                                                                             \
+    _Pragma("unroll") for (int i = 0; i < FM; ++i) _Pragma("unroll") for (int j = 0; j < FN; ++j) acc[i][j] =   \
+        __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);                    \
+  }
+#define SB() __builtin_amdgcn_sched_barrier(0)
+  // wait for this wave's LDS reads and global->LDS loads, then meet the other waves
+#define SYNC()                                    \
+  {                                               \
+    __builtin_amdgcn_s_waitcnt(0x0070);           \
+    __builtin_amdgcn_s_barrier();                 \
+    asm volatile("" ::: "memory");                \
+  }
+  // Slice j sits in (ca, cb); slice j + 1 goes to (na, nb).  On entry fragment set 1 holds k-step 3
+  // of the previous slice (garbage-free zeros for the first slice: see below).
+#define SLICE_STEP(ca, cb, na, nb, first)                                 \
+  {                                                                       \
+    ISSUE(na, nb, min(j + 1, nk - 1));                                    \
+    FETCH(0, ca, cb, 0);                                                  \
+    SB();                                                                 \
+    if (!(first)) MMA(1);                                                 \
+    SB();                                                                 \
+    FETCH(1, ca, cb, 1);                                                  \
+    SB();                                                                 \
+    MMA(0);                                                               \
+    SB();                                                                 \
+    FETCH(0, ca, cb, 2);                                                  \
+    SB();                                                                 \
+    MMA(1);                                                               \
+    SB();                                                                 \
+    FETCH(1, ca, cb, 3);                                                  \
+    SB();                                                                 \
+    MMA(0);                                                               \
+    SB();                                                                 \
+    SYNC();                                                               \
+    ++j;                                                                  \
   }
 
-  // ---- epilogue: scale, add diag / R, round to bf16, stage in LDS, coalesced stores
+  const int nk = K / BK;
+  int j = 0;
+  ISSUE(sA0, sB0, 0);
+  SYNC();
+  // first slice: no pending k-step from a previous slice
+  SLICE_STEP(sA0, sB0, sA1, sB1, true);
+  // Past the end the issue re-reads the last slice (never consumed), so every step has the same shape.
+  while (j + 1 < nk) {
+    SLICE_STEP(sA1, sB1, sA0, sB0, false);
+    SLICE_STEP(sA0, sB0, sA1, sB1, false);
+  }
+  if (j < nk) SLICE_STEP(sA1, sB1, sA0, sB0, false);
+  MMA(1);  // k-step 3 of the last slice
+#undef SLICE_STEP
+#undef SYNC
+#undef SB
+#undef FETCH
+#undef MMA
+#undef ISSUE
+
+  // ---- epilogue straight from the accumulators: a lane holds row m and 4 consecutive columns
   float s = 1.f;
   if (P.scale && args.scale_pow) {
     s = P.scale[b];
@@ -137,119 +250,193 @@ __global__ void __launch_bounds__(NTHREADS) sm_ns_gemm_nt_kernel(const sm_gemm_a
   }
   const float alpha = args.alpha * s;
   const bf16_t* __restrict__ R = P.R ? P.R + (long long)b * P.sC : nullptr;
-  bf16_t* Cs = reinterpret_cast<bf16_t*>(smem);  // [BM][CS]; the K loop ended with a barrier
-#pragma unroll
-  for (int i = 0; i < FM; ++i) {
-    const int ml = w_m * WM + i * 32 + fr;
-    const int mg = m0 + ml;
-#pragma unroll
-    for (int j = 0; j < FN; ++j) {
-#pragma unroll
-      for (int vg = 0; vg < 4; ++vg) {
-        const int nl = w_n * WN + j * 32 + 8 * vg + 4 * fg;
-        const int ng = n0 + nl;
-        float o[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          o[e] = alpha * acc[i][j][4 * vg + e];
-          if (mg == ng + e) o[e] += args.diag;
-        }
-        if (R && mg < M && ng < N) {
-          const bf16x4 rv = *reinterpret_cast<const bf16x4*>(R + (long long)mg * P.ldc + ng);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] += args.gamma * (float)rv[e];
-        }
-        const bf16x4 h = {(bf16_t)o[0], (bf16_t)o[1], (bf16_t)o[2], (bf16_t)o[3]};
-        *reinterpret_cast<bf16x4*>(Cs + ml * CS + nl) = h;
-      }
-    }
-  }
-  __syncthreads();
   bf16_t* __restrict__ C = P.C + (long long)b * P.sC;
-  constexpr int CPR = BN / 8;  // 16-byte chunks per tile row
+  const int fr = lane & 31, fg = lane >> 5;
+  const bool mirror = SYM && (tm != tn);
+  // The tile leaves through LDS so that every global store is a 16-byte piece of a full row
+  // segment (TS * 2 bytes contiguous).  The four stage arrays hold 64 tile rows each (rows of
+  // TS * 2 bytes, 16-byte chunk c of row r at slot c ^ (r & (CPR - 1))).  Pass 0 stages the
+  // tile as computed; pass 1 (off-diagonal tiles of a symmetric output) stages its transpose.
+  constexpr int RB = TS * 2, CPR = TS / 8, RPP = NTH / CPR, PASSES = TS / RPP;
+  auto stage = [&](int idx) -> unsigned char* { return idx == 0 ? sA0 : idx == 1 ? sA1 : idx == 2 ? sB0 : sB1; };
 #pragma unroll
-  for (int it = 0; it < BM * CPR / NTHREADS; ++it) {
-    const int q = it * NTHREADS + tid;
-    const int r = q / CPR, cc = q % CPR;
-    const int mg = m0 + r, ng = n0 + cc * 8;
-    if (mg < M && ng < N) {
-      const bf16x4 lo = *reinterpret_cast<const bf16x4*>(Cs + r * CS + cc * 8);
-      const bf16x4 hi = *reinterpret_cast<const bf16x4*>(Cs + r * CS + cc * 8 + 4);
-      bf16x8 v;
+  for (int pass = 0; pass < 2; ++pass) {
+    if (pass == 1 && !mirror) break;
+    if (pass == 1) __syncthreads();  // pass 0 has been read out
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        v[e] = lo[e];
-        v[e + 4] = hi[e];
+    for (int i = 0; i < FM; ++i) {
+      const int ml = w_m * WM + i * 32 + fr;  // tile row of this lane
+      const int mg = m0 + ml;
+#pragma unroll
+      for (int jn = 0; jn < FN; ++jn) {
+#pragma unroll
+        for (int vg = 0; vg < 4; ++vg) {
+          const int nl = w_n * WN + jn * 32 + 8 * vg + 4 * fg;  // first of 4 tile columns
+          const int ng = n0 + nl;
+          float o[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            o[e] = alpha * acc[i][jn][4 * vg + e];
+            if (mg == ng + e) o[e] += args.diag;
+          }
+          if (R && mg < M && ng < N) {
+            const bf16x4 rv = *reinterpret_cast<const bf16x4*>(R + (long long)mg * P.ldc + ng);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] += args.gamma * (float)rv[e];
+          }
+          const bf16x4 h = {(bf16_t)o[0], (bf16_t)o[1], (bf16_t)o[2], (bf16_t)o[3]};
+          if (pass == 0) {
+            // rows w_m*WM + i*32 .. +31 lie in one stage array (64 rows each): uniform choice
+            unsigned char* sp = stage((w_m * WM + i * 32) >> 6);
+            const int r = ml & 63;
+            *reinterpret_cast<bf16x4*>(sp + r * RB + ((((nl >> 3) ^ (ml & (CPR - 1)))) << 4) + (nl & 7) * 2) = h;
+          } else {
+            // transposed: element (ml, nl + e) goes to row nl + e, column ml
+            unsigned char* sp = stage((w_n * WN + jn * 32) >> 6);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int tr = nl + e;
+              *reinterpret_cast<bf16_t*>(sp + (tr & 63) * RB + ((((ml >> 3) ^ (tr & (CPR - 1)))) << 4) + (ml & 7) * 2) = h[e];
+            }
+          }
+        }
       }
-      *reinterpret_cast<bf16x8*>(C + (long long)mg * P.ldc + ng) = v;
+    }
+    __syncthreads();
+    // read out: thread t handles chunk t % CPR of rows t / CPR + RPP * k
+    const int rc = tid % CPR, rr = tid / CPR;
+    const int row_base = (pass == 0) ? m0 : n0, col_base = (pass == 0) ? n0 : m0;
+    const int rows_lim = (pass == 0) ? M : N, cols_lim = (pass == 0) ? N : M;
+#pragma unroll
+    for (int k = 0; k < PASSES; ++k) {
+      const int row = rr + RPP * k;  // tile row; (row >> 6) == (RPP * k) >> 6 is a constant
+      const unsigned char* sp = stage((RPP * k) >> 6);
+      const u32x4 v = *reinterpret_cast<const u32x4*>(sp + (row & 63) * RB + ((rc ^ (row & (CPR - 1))) << 4));
+      const int gr = row_base + row, gc = col_base + rc * 8;
+      if (gr < rows_lim && gc < cols_lim) *reinterpret_cast<u32x4*>(C + (long long)gr * P.ldc + gc) = v;
     }
   }
 }
 
-template <int BM, int BN>
-constexpr size_t gemm_lds_bytes() {
-  const size_t loop = 2ull * (BM + BN) * BK * 2;
-  const size_t epi = (size_t)BM * (BN + 4) * 2;
-  return loop > epi ? loop : epi;
+// KIND 0: Gram half-step (symmetric output; operands both KC or both MN).
+// KIND 1: apply half-step (A is KC; B is KC or MN).
+template <int KIND, int TS>
+__global__ void __launch_bounds__(NTH) sm_ns_gemm_kernel(const sm_gemm_args args) {
+  constexpr bool SYM = (KIND == 0);
+  __shared__ __attribute__((aligned(1024))) unsigned char sA0[TS * 128], sA1[TS * 128];
+  __shared__ __attribute__((aligned(1024))) unsigned char sB0[TS * 128], sB1[TS * 128];
+
+  // Persistent workgroups: the grid is one (TS = 256) or two (TS = 128) workgroups per CU and each
+  // walks a list of tiles, so the global stores of one tile drain while the next tile is loaded
+  // and multiplied.  Workgroup ids are dealt round-robin to the 8 XCDs: XCD x owns the contiguous
+  // eighth [x * tiles_per_xcd, (x + 1) * tiles_per_xcd) of the tile list and its workgroups take
+  // neighbouring tiles at any one time, so tiles that share operand panels share an L2.
+  const int wg = blockIdx.x;
+  const int per_xcd_wgs = gridDim.x >> 3;
+  const int xcd_end = min((int)(((wg & 7) + 1) * args.tiles_per_xcd), args.total_tiles);
+  bool first_tile = true;
+  for (int L = (wg & 7) * args.tiles_per_xcd + (wg >> 3); L < xcd_end; L += per_xcd_wgs) {
+    if (!first_tile) __syncthreads();  // the previous tile has been read out of the stage arrays
+    first_tile = false;
+    int pi = 0;
+    while (pi + 1 < args.n_prob && L >= args.p[pi + 1].tile_begin) ++pi;
+    const sm_gemm_prob& P = args.p[pi];
+    int t = L - P.tile_begin;
+    const int per_batch = SYM ? P.tiles_m * (P.tiles_m + 1) / 2 : P.tiles_m * P.tiles_n;
+    const int b = t / per_batch;
+    t -= b * per_batch;
+    int tm, tn;
+    if (SYM) {  // upper triangle, column by column: (0,0) (0,1) (1,1) (0,2) ...
+      tn = 0;
+      while (t > tn) {
+        t -= tn + 1;
+        ++tn;
+      }
+      tm = t;
+    } else {
+      tn = t / P.tiles_m;
+      tm = t - tn * P.tiles_m;
+    }
+    if (KIND == 0) {
+      if (P.layout == 0)
+        gemm_tile<TS, false, false, true>(args, P, b, tm, tn, sA0, sA1, sB0, sB1);
+      else
+        gemm_tile<TS, true, true, true>(args, P, b, tm, tn, sA0, sA1, sB0, sB1);
+    } else {
+      if (P.layout == 0)
+        gemm_tile<TS, false, false, false>(args, P, b, tm, tn, sA0, sA1, sB0, sB1);
+      else
+        gemm_tile<TS, false, true, false>(args, P, b, tm, tn, sA0, sA1, sB0, sB1);
+    }
+  }
 }
 
-template <int BM, int BN, int WM, int WN, int KIND>
-int launch_cfg(signmuon_ctx* ctx, sm_gemm_args& args, int klass) {
+// tile bookkeeping shared by every instantiation
+static void fill_tiles(sm_gemm_args& args, bool sym, int ts) {
   int total = 0;
   for (int i = 0; i < args.n_prob; ++i) {
     sm_gemm_prob& P = args.p[i];
-    P.tiles_m = (P.M + BM - 1) / BM;
-    P.tiles_n = (P.N + BN - 1) / BN;
+    P.tiles_m = (P.M + ts - 1) / ts;
+    P.tiles_n = (P.N + ts - 1) / ts;
     P.tile_begin = total;
-    total += P.tiles_m * P.tiles_n * P.batch;
+    total += (sym ? P.tiles_m * (P.tiles_m + 1) / 2 : P.tiles_m * P.tiles_n) * P.batch;
   }
   args.total_tiles = total;
   args.tiles_per_xcd = (total + 7) / 8;
-  if (total == 0) return SM_OK;
-  auto kern = sm_ns_gemm_nt_kernel<BM, BN, WM, WN, KIND>;
-  constexpr size_t lds = gemm_lds_bytes<BM, BN>();
-  static bool attr_done = false;
-  if (!attr_done) {
-    SM_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)lds));
-    attr_done = true;
-  }
-  {
-    sm_launch_scope sc(ctx, klass);
-    hipLaunchKernelGGL(kern, dim3(args.tiles_per_xcd * 8), dim3(NTHREADS), lds, ctx->stream, args);
-  }
-  SM_HIP(ctx, hipGetLastError());
-  return SM_OK;
 }
 
-}  // namespace
+}  // namespace sm_gemm
+using namespace sm_gemm;
 
-int sm_gemm_tile_override = 0;  // 0: automatic; 128 or 256 forces a tile size (tuning aid)
-
-int sm_launch_gemm_nt(signmuon_ctx* ctx, sm_gemm_args& args, int klass) {
+// Per problem, P.layout bit 0: A is MN-contiguous, bit 1: B is MN-contiguous.  klass SM_K_NS_GRAM:
+// A == B, symmetric output, layout 0 or 3.  klass SM_K_NS_APPLY: layout 0 or 2.  K multiple of 64.
+int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, int klass) {
+  const bool gram = (klass == SM_K_NS_GRAM);
   for (int i = 0; i < args.n_prob; ++i) {
     const sm_gemm_prob& P = args.p[i];
     if (P.M % 64 || P.N % 64 || P.K % 64 || P.lda % 8 || P.ldb % 8 || P.ldc % 8 || !sm_aligned(P.A, 16) ||
-        !sm_aligned(P.B, 16) || !sm_aligned(P.C, 16) || P.sA % 8 || P.sB % 8 || P.sC % 8)
+        !sm_aligned(P.B, 16) || !sm_aligned(P.C, 16) || P.sA % 8 || P.sB % 8 || P.sC % 8 || (gram && P.M != P.N))
       return sm_fail(ctx, SM_EINVAL, "internal: GEMM operand not padded/aligned");
+    if (gram ? (P.layout != 0 && P.layout != 3) : (P.layout != 0 && P.layout != 2))
+      return sm_fail(ctx, SM_EUNSUPPORTED, "internal: GEMM layout combination not built");
+    // buffer offsets are 32-bit
+    const long long a_ext = (P.layout & 1) ? (long long)P.K * P.lda : (long long)P.M * P.lda;
+    const long long b_ext = (P.layout & 2) ? (long long)P.K * P.ldb : (long long)P.N * P.ldb;
+    if (a_ext * 2 >= 0x7FFFFFFFLL || b_ext * 2 >= 0x7FFFFFFFLL)
+      return sm_fail(ctx, SM_EUNSUPPORTED, "internal: GEMM operand larger than 2 GiB");
   }
   static const int env_tile = [] {
     const char* e = getenv("SIGNMUON_GEMM_TILE");
     return e ? atoi(e) : 0;
   }();
-  int tile = sm_gemm_tile_override ? sm_gemm_tile_override : env_tile;
-  if (tile == 0) {
-    // large tiles once there is enough work to fill 256 CUs with them
-    long long t256 = 0;
-    for (int i = 0; i < args.n_prob; ++i) {
-      const sm_gemm_prob& P = args.p[i];
-      t256 += (long long)((P.M + 255) / 256) * ((P.N + 255) / 256) * P.batch;
-    }
-    tile = (t256 >= 512) ? 256 : 128;
+  int ts = env_tile;
+  if (ts != 128 && ts != 256) {
+    // 256 x 256 tiles once there are enough of them to keep 256 CUs busy for several rounds
+    fill_tiles(args, gram, 256);
+    ts = (args.total_tiles >= 1024) ? 256 : 128;
   }
-  const bool gram = (klass == SM_K_NS_GRAM);
-  if (tile == 256) {
-    return gram ? launch_cfg<256, 256, 128, 128, 0>(ctx, args, klass) : launch_cfg<256, 256, 128, 128, 1>(ctx, args, klass);
+  fill_tiles(args, gram, ts);
+  if (args.total_tiles == 0) return SM_OK;
+  // persistent grid: one workgroup per CU (two for the small tile), a multiple of 8, never more than tiles
+  static const int n_cu = [] {
+    int dev = 0, n = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+    return n;
+  }();
+  int wgs = n_cu * (ts == 128 ? 2 : 1);
+  wgs = std::min(wgs / 8, args.tiles_per_xcd) * 8;
+  const dim3 grid(wgs), block(NTH);
+  {
+    sm_launch_scope sc(ctx, klass);
+    if (gram && ts == 256)
+      hipLaunchKernelGGL((sm_ns_gemm_kernel<0, 256>), grid, block, 0, ctx->stream, args);
+    else if (gram)
+      hipLaunchKernelGGL((sm_ns_gemm_kernel<0, 128>), grid, block, 0, ctx->stream, args);
+    else if (ts == 256)
+      hipLaunchKernelGGL((sm_ns_gemm_kernel<1, 256>), grid, block, 0, ctx->stream, args);
+    else
+      hipLaunchKernelGGL((sm_ns_gemm_kernel<1, 128>), grid, block, 0, ctx->stream, args);
   }
-  return gram ? launch_cfg<128, 128, 64, 64, 0>(ctx, args, klass) : launch_cfg<128, 128, 64, 64, 1>(ctx, args, klass);
+  SM_HIP(ctx, hipGetLastError());
+  return SM_OK;
 }
