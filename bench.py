@@ -78,9 +78,10 @@ def run_workload(name, steps, warmup, torch, P, B):
     for _ in range(warmup):
         P.signmuon_step(ctx, plan)
     torch.cuda.synchronize()
-    # timed region: only the two GEMM classes carry event taps here (a few dozen launches per step)
+    # timed region: only the GEMM classes carry event taps here (a few dozen launches per step)
+    gemm_classes = (B.SM_K_NS_GRAM, B.SM_K_NS_SMALL, B.SM_K_NS_APPLY)
     ctx.profile_reset()
-    ctx.profile_enable((1 << B.SM_K_NS_GRAM) | (1 << B.SM_K_NS_APPLY))
+    ctx.profile_enable(sum(1 << k for k in gemm_classes))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
@@ -88,8 +89,20 @@ def run_workload(name, steps, warmup, torch, P, B):
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     elapsed = t1 - t0
-    n_gram, ms_gram = ctx.profile_read(B.SM_K_NS_GRAM)
-    n_apply, ms_apply = ctx.profile_read(B.SM_K_NS_APPLY)
+    gemm = {}
+    for k in gemm_classes:
+        n, ms = ctx.profile_read(k)
+        flop, nbytes = ctx.profile_work(k)
+        if n == 0:
+            continue
+        sec = ms * 1e-3
+        t_mfma, t_hbm = flop / (MFMA_BF16_PEAK_TFLOPS * 1e12), nbytes / (HBM_PEAK_GBS * 1e9)
+        gemm[P.kernel_name(k)] = {
+            "launches_per_step": n / steps, "avg_launch_ms": ms / n, "ms_per_step": ms / steps,
+            "flop_per_launch": flop / n, "bytes_per_launch": nbytes / n,
+            "tflops": flop / sec / 1e12, "gbs": nbytes / sec / 1e9,
+            "bound": "mfma" if t_mfma >= t_hbm else "hbm",
+        }
     # second, untimed pass with taps on every kernel class: per-class breakdown
     ctx.profile_reset()
     ctx.profile_enable((1 << B.SM_K_COUNT) - 1)
@@ -105,9 +118,9 @@ def run_workload(name, steps, warmup, torch, P, B):
     ctx.close()
 
     d_total = sum(r * c for r, c in shapes)
-    g1, a1 = ns_flops(shapes, M, K)
-    g2, a2 = ns_flops(shapes, 1, Kp)
-    gram_flop, apply_flop = g1 + g2, a1 + a2
+    nominal = sum(ns_flops(shapes, M, K)) + sum(ns_flops(shapes, 1, Kp))
+    ns_ms = sum(g["ms_per_step"] for g in gemm.values())
+    executed = sum(g["flop_per_launch"] * g["launches_per_step"] for g in gemm.values())
     one_bit = cfg["sign_fmt"] == "1bit"
     pack_bytes = d_total * M * (2 + (0.125 if one_bit else 1.0))
     if Kp:
@@ -121,12 +134,11 @@ def run_workload(name, steps, warmup, torch, P, B):
     res = {
         "workload": name, "M": M, "n_blocks": len(shapes), "entries": d_total,
         "steps_per_s": steps / elapsed, "ms_per_step": 1e3 * elapsed / steps,
-        "ns_tflops": (gram_flop + apply_flop) * steps / ((ms_gram + ms_apply) * 1e-3) / 1e12 if ms_gram + ms_apply else None,
-        "ns_gram": {"launches": n_gram, "avg_ms": ms_gram / max(n_gram, 1),
-                    "tflops": gram_flop * steps / (ms_gram * 1e-3) / 1e12 if ms_gram else None},
-        "ns_apply": {"launches": n_apply, "avg_ms": ms_apply / max(n_apply, 1),
-                     "tflops": apply_flop * steps / (ms_apply * 1e-3) / 1e12 if ms_apply else None,
-                     "flop_per_launch": apply_flop * steps / max(n_apply, 1)},
+        # nominal: the work of Alg. PolarNS as written (4 s^2 l per step and matrix) over the time of all
+        # Newton-Schulz launches; executed: the matrix products actually launched
+        "ns_tflops": nominal / (ns_ms * 1e-3) / 1e12 if ns_ms else None,
+        "ns_tflops_executed": executed / (ns_ms * 1e-3) / 1e12 if ns_ms else None,
+        "ns_ms_per_step": ns_ms, "gemm": gemm,
         "sign_vote_gbs": (pack_bytes + vote_bytes) / ((ms_pack + ms_vote) * 1e-3) / 1e9 if ms_pack + ms_vote else None,
         "momentum_gbs": mom_bytes / (ms_mom * 1e-3) / 1e9 if ms_mom else None,
         "per_class": per_class, "workspace_GB": ws / 1e9,
@@ -217,14 +229,19 @@ def main():
     also = None
     if args.also and args.also != args.workload:
         also = run_workload(args.also, max(args.steps * 5, 50), args.warmup, torch, P, B)
+    # roofline of the dominant kernel: the GEMM class with the largest share of the step
+    dom_name, dom = max(main_res["gemm"].items(), key=lambda kv: kv[1]["ms_per_step"])
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(args.workload, {}).get("ns_apply_bytes_per_launch")
+            traffic = json.load(open(tpath)).get(args.workload, {}).get(dom_name)
         except Exception:
             traffic = None
-    ach = main_res["ns_apply"]["tflops"]
+    if dom["bound"] == "mfma":
+        ach, peak, unit = dom["tflops"], MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
+    else:
+        ach, peak, unit = dom["gbs"], HBM_PEAK_GBS, "GB/s"
     line = {
         "metric": "Sign-Muon steps/sec; NS TFLOPS (% MFMA peak); sign+vote GB/s (% HBM)",
         "value": main_res["steps_per_s"], "unit": "steps/s", "n_gpus": 1,
@@ -233,13 +250,13 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "M": main_res["M"], "blocks": main_res["n_blocks"],
                    "entries": main_res["entries"], "ns_steps": 5, "scale": "fro"},
-        "roofline": {"kernel": "sm_ns_gemm_kernel<1, 256> (apply half-step)", "bound": "mfma", "achieved": ach,
-                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": (ach / MFMA_BF16_PEAK_TFLOPS) if ach else None, "traffic": traffic,
-                     "avg_launch_ms": main_res["ns_apply"]["avg_ms"],
-                     "flop_per_launch": main_res["ns_apply"]["flop_per_launch"]},
-        "ns": {"tflops": main_res["ns_tflops"], "frac_of_mfma_peak": main_res["ns_tflops"] / MFMA_BF16_PEAK_TFLOPS
-               if main_res["ns_tflops"] else None, "gram": main_res["ns_gram"], "apply": main_res["ns_apply"]},
+        "roofline": {"kernel": dom_name, "bound": dom["bound"], "achieved": ach, "peak": peak, "unit": unit,
+                     "frac": ach / peak, "traffic": traffic, "avg_launch_ms": dom["avg_launch_ms"],
+                     "flop_per_launch": dom["flop_per_launch"], "bytes_per_launch": dom["bytes_per_launch"]},
+        "ns": {"tflops": main_res["ns_tflops"],
+               "frac_of_mfma_peak": main_res["ns_tflops"] / MFMA_BF16_PEAK_TFLOPS if main_res["ns_tflops"] else None,
+               "tflops_executed": main_res["ns_tflops_executed"], "ms_per_step": main_res["ns_ms_per_step"],
+               "gemm": main_res["gemm"]},
         "sign_vote": {"gbs": main_res["sign_vote_gbs"],
                       "frac_of_hbm_peak": main_res["sign_vote_gbs"] / HBM_PEAK_GBS if main_res["sign_vote_gbs"] else None},
         "momentum_gbs": main_res["momentum_gbs"],

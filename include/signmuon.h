@@ -176,10 +176,16 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* args);
 #define SM_K_VOTE 4
 #define SM_K_UPDATE 5
 #define SM_K_OTHER 6
-#define SM_K_COUNT 7
+#define SM_K_NS_SMALL 7
+#define SM_K_COUNT 8
 int signmuon_profile_enable(signmuon_ctx* ctx, unsigned class_mask);
 int signmuon_profile_reset(signmuon_ctx* ctx);
 int signmuon_profile_read(signmuon_ctx* ctx, int kernel_class, int64_t* launches, double* total_ms);
+/* Work booked by the timed launches of a GEMM class since the last reset:
+ * flop = sum of 2*M*N*K over the matrix products as written (a symmetric product
+ * counts in full although only its upper triangle of tiles is computed), bytes =
+ * their operands and results, each counted once.  Zero for the other classes. */
+int signmuon_profile_work(signmuon_ctx* ctx, int kernel_class, double* flop, double* bytes);
 const char* signmuon_kernel_name(int kernel_class);
 
 #ifdef __cplusplus

@@ -22,7 +22,7 @@ SM_SCALE_FRO, SM_SCALE_SPECTRAL, SM_SCALE_NONE = 0, 1, 2
 SM_SIGN_1BIT, SM_SIGN_INT8 = 0, 1
 SM_VOTE_BITS, SM_VOTE_INT8, SM_VOTE_BF16, SM_VOTE_F32 = 0, 1, 2, 3
 (SM_K_MOMENTUM, SM_K_NS_GRAM, SM_K_NS_APPLY, SM_K_SIGN_PACK, SM_K_VOTE,
- SM_K_UPDATE, SM_K_OTHER, SM_K_COUNT) = range(8)
+ SM_K_UPDATE, SM_K_OTHER, SM_K_NS_SMALL, SM_K_COUNT) = range(9)
 
 SCALES = {"fro": SM_SCALE_FRO, "spectral": SM_SCALE_SPECTRAL, "none": SM_SCALE_NONE}
 SIGN_FMTS = {"1bit": SM_SIGN_1BIT, "int8": SM_SIGN_INT8}
@@ -32,7 +32,7 @@ EXPORTS = [
     "signmuon_create", "signmuon_destroy", "signmuon_strerror", "signmuon_last_error",
     "signmuon_workspace_bytes", "signmuon_momentum", "signmuon_polar_ns", "signmuon_sign_pack",
     "signmuon_majority_vote", "signmuon_step", "signmuon_profile_enable", "signmuon_profile_reset",
-    "signmuon_profile_read", "signmuon_kernel_name",
+    "signmuon_profile_read", "signmuon_profile_work", "signmuon_kernel_name",
 ]
 
 
@@ -73,6 +73,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.signmuon_profile_enable.argtypes = [vp, C.c_uint]
     lib.signmuon_profile_reset.argtypes = [vp]
     lib.signmuon_profile_read.argtypes = [vp, i32, C.POINTER(i64), C.POINTER(C.c_double)]
+    lib.signmuon_profile_work.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.signmuon_kernel_name.argtypes = [i32]
     lib.signmuon_kernel_name.restype = C.c_char_p
     return lib
@@ -147,6 +148,11 @@ class Context:
         n, ms = C.c_int64(), C.c_double()
         self._check(_lib.signmuon_profile_read(self._h, kernel_class, C.byref(n), C.byref(ms)), "profile_read")
         return n.value, ms.value
+
+    def profile_work(self, kernel_class):
+        fl, by = C.c_double(), C.c_double()
+        self._check(_lib.signmuon_profile_work(self._h, kernel_class, C.byref(fl), C.byref(by)), "profile_work")
+        return fl.value, by.value
 
 
 def kernel_name(kernel_class):

@@ -6,6 +6,8 @@
 // through the iteration, so they change nothing).  One grouped GEMM launch then
 // covers every class, block and worker of a Newton-Schulz half-step.
 #include <math.h>
+#include <stdlib.h>
+#include <string.h>
 
 #include <algorithm>
 
@@ -20,14 +22,15 @@ struct ns_class {
   std::vector<int> members;
   long long mat = 0;       // rp * cp
   // arena offsets in bytes
-  size_t off_x[2] = {0, 0}, off_b = 0, off_a = 0, off_sig = 0, off_inv = 0, off_partial = 0;
+  size_t off_x[2] = {0, 0}, off_sig = 0, off_inv = 0, off_partial = 0;
+  // s x s matrices per item: Q (two buffers), A, T, P (two buffers)
+  size_t off_q[2] = {0, 0}, off_a = 0, off_t = 0, off_p[2] = {0, 0};
   int chunks = 0;          // momentum chunks per worker
 };
 
 struct ns_plan {
   std::vector<int> rows, cols;
   int M = 0;
-  bool quintic = false;
   int sign_fmt = -1;
   std::vector<ns_class> classes;
   std::vector<int> class_of, index_in_class;  // per block
@@ -51,10 +54,10 @@ T* at(signmuon_ctx* ctx, size_t off) {
   return reinterpret_cast<T*>(reinterpret_cast<unsigned char*>(ctx->arena) + off);
 }
 
-int get_plan(signmuon_ctx* ctx, int n, const int* rows, const int* cols, int M, bool quintic, int sign_fmt,
+int get_plan(signmuon_ctx* ctx, int n, const int* rows, const int* cols, int M, int sign_fmt,
              ns_plan** out) {
   ns_plan* pl = ctx->plan;
-  if (pl && pl->M == M && pl->quintic == quintic && pl->sign_fmt == sign_fmt && (int)pl->rows.size() == n &&
+  if (pl && pl->M == M && pl->sign_fmt == sign_fmt && (int)pl->rows.size() == n &&
       std::equal(rows, rows + n, pl->rows.begin()) && std::equal(cols, cols + n, pl->cols.begin())) {
     *out = pl;
     return SM_OK;
@@ -64,7 +67,6 @@ int get_plan(signmuon_ctx* ctx, int n, const int* rows, const int* cols, int M, 
   pl->rows.assign(rows, rows + n);
   pl->cols.assign(cols, cols + n);
   pl->M = M;
-  pl->quintic = quintic;
   pl->sign_fmt = sign_fmt;
   pl->class_of.resize(n);
   pl->index_in_class.resize(n);
@@ -101,8 +103,13 @@ int get_plan(signmuon_ctx* ctx, int n, const int* rows, const int* cols, int M, 
     const long long batch = (long long)c.count * M;
     c.off_x[0] = take((size_t)batch * c.mat * 2);
     c.off_x[1] = take((size_t)batch * c.mat * 2);
-    c.off_b = take((size_t)batch * c.s * c.s * 2);
-    c.off_a = quintic ? take((size_t)batch * c.s * c.s * 2) : 0;
+    const size_t ssb = (size_t)batch * c.s * c.s * 2;
+    c.off_q[0] = take(ssb);
+    c.off_q[1] = take(ssb);
+    c.off_a = take(ssb);
+    c.off_t = take(ssb);
+    c.off_p[0] = take(ssb);
+    c.off_p[1] = take(ssb);
     c.off_sig = take((size_t)batch * 4);
     c.off_inv = take((size_t)batch * 4);
     c.off_partial = take((size_t)batch * c.chunks * 4);
@@ -129,106 +136,276 @@ int get_plan(signmuon_ctx* ctx, int n, const int* rows, const int* cols, int M, 
   return SM_OK;
 }
 
-// Runs `steps` Newton-Schulz steps on every class, batch = count * mult per class,
-// starting from buffer `cur` (0/1) of each class.  Scales the first step by the
-// per-item inv_sigma when use_scale.  Returns the buffer index holding the result.
-// Per step: one Gram launch and one apply launch over all classes.  Classes with rows <= cols
-// take the Gram over the rows (Bm = a I + b Y Y^T, Y' = Bm Y), the others over the columns
-// (Bm = a I + b Y^T Y, Y' = Y Bm).  Y is read in place in both.
-int run_ns(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coeffs, bool use_scale, int* cur_io) {
+// ---- grouped GEMM launches over the classes of a plan
+struct gemm_params {
+  float alpha = 1.f, gamma = 0.f, diag = 0.f, alpha2 = 0.f, diag2 = 0.f;
+  int scale_pow = 0;
+  bool sym = true;
+  bool in_f16 = false, out_f16 = false;
+  int klass = SM_K_NS_SMALL;
+};
+
+// fill(cl, P) sets up `per_class` consecutive problems for class cl (everything except the tile
+// bookkeeping); classes are spread over as many launches as the problem table needs.
+template <typename F>
+int launch_over_classes(signmuon_ctx* ctx, ns_plan* pl, const gemm_params& gp, int per_class, F fill) {
+  const size_t ncls = pl->classes.size();
+  const size_t per_launch = SM_GEMM_MAX_PROB / per_class;
+  for (size_t c0 = 0; c0 < ncls; c0 += per_launch) {
+    const int g = (int)std::min(ncls - c0, per_launch);
+    sm_gemm_args ga;
+    ga.in_f16 = gp.in_f16;
+    ga.out_f16 = gp.out_f16;
+    ga.alpha = gp.alpha;
+    ga.gamma = gp.gamma;
+    ga.diag = gp.diag;
+    ga.alpha2 = gp.alpha2;
+    ga.diag2 = gp.diag2;
+    ga.scale_pow = gp.scale_pow;
+    for (int i = 0; i < g; ++i) {
+      sm_gemm_prob* P = &ga.p[i * per_class];
+      for (int j = 0; j < per_class; ++j) {
+        P[j].C2 = nullptr;
+        P[j].R = nullptr;
+        P[j].scale = nullptr;
+        P[j].layout = 0;
+      }
+      fill(pl->classes[c0 + i], P);
+    }
+    ga.n_prob = g * per_class;
+    const int rc = sm_launch_gemm(ctx, ga, gp.sym, gp.klass);
+    if (rc != SM_OK) return rc;
+  }
+  return SM_OK;
+}
+
+// C[s][s] from the short side of Y: Y Y^T (rows <= cols; Y's rows are K-contiguous) or Y^T Y.
+void gram_of_y(ns_class& cl, sm_gemm_prob& P, const bf16_t* y, bf16_t* c, int batch) {
+  P.A = P.B = y;
+  P.C = c;
+  P.sA = P.sB = cl.mat;
+  P.sC = (long long)cl.s * cl.s;
+  P.M = P.N = cl.s;
+  P.K = cl.l;
+  P.lda = P.ldb = cl.cp;
+  P.ldc = cl.s;
+  P.layout = cl.wide ? 0 : 3;
+  P.batch = batch;
+}
+
+// Y'[rp][cp] = S Y (rows <= cols; second operand stored [K][N]) or Y S, S symmetric s x s.
+void apply_to_y(ns_class& cl, sm_gemm_prob& P, const bf16_t* sm, const bf16_t* y, bf16_t* yout, int batch) {
+  const long long ss = (long long)cl.s * cl.s;
+  P.C = yout;
+  P.sC = cl.mat;
+  P.M = cl.rp;
+  P.N = cl.cp;
+  P.ldc = cl.cp;
+  P.K = cl.s;
+  P.batch = batch;
+  if (cl.wide) {
+    P.A = sm;
+    P.B = y;
+    P.sA = ss;
+    P.sB = cl.mat;
+    P.lda = cl.s;
+    P.ldb = cl.cp;
+    P.layout = 2;
+  } else {
+    P.A = y;
+    P.B = sm;
+    P.sA = cl.mat;
+    P.sB = ss;
+    P.lda = cl.cp;
+    P.ldb = cl.s;
+    P.layout = 0;
+  }
+}
+
+// C = A B^T over s x s symmetric matrices (all K-contiguous).
+void small_product(ns_class& cl, sm_gemm_prob& P, const bf16_t* a, const bf16_t* b, bf16_t* c, int batch) {
+  P.A = a;
+  P.B = b;
+  P.C = c;
+  P.sA = P.sB = P.sC = (long long)cl.s * cl.s;
+  P.M = P.N = P.K = cl.s;
+  P.lda = P.ldb = P.ldc = cl.s;
+  P.layout = 0;
+  P.batch = batch;
+}
+
+// Step-by-step form of Alg. PolarNS: per step one Gram launch (Bm = a I + b G [+ c G^2], G the
+// Gram matrix of Y over its short side) and one apply launch (Y' = Bm Y or Y Bm) over all
+// classes; batch = count * mult per class, starting from buffer `cur` (0/1) of each class.
+// The first step carries the per-item 1 / sigma when use_scale.  Y is read in place.
+int run_ns_stepwise(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coeffs, bool use_scale,
+                    int* cur_io) {
   int cur = *cur_io;
   const float a = coeffs[0], b = coeffs[1], c = coeffs[2];
   for (int k = 0; k < steps; ++k) {
     const bool sc = use_scale && k == 0;
-    for (int phase = 0; phase < 2; ++phase) {      // 0: Gram, 1: apply
-      const size_t ncls = pl->classes.size();
-      for (size_t c0 = 0; c0 < ncls; c0 += SM_GEMM_MAX_PROB) {
-        const int g = (int)std::min(ncls - c0, (size_t)SM_GEMM_MAX_PROB);
-        sm_gemm_args ga;
-        ga.n_prob = g;
-        ga.pad_ = 0;
-        ga.gamma = 0.f;
-        if (phase == 0) {
-          ga.scale_pow = sc ? 2 : 0;
-          ga.alpha = (c != 0.f) ? 1.f : b;
-          ga.diag = (c != 0.f) ? 0.f : a;
-        } else {
-          ga.scale_pow = sc ? 1 : 0;
-          ga.alpha = 1.f;
-          ga.diag = 0.f;
-        }
-        for (int i = 0; i < g; ++i) {
-          ns_class& cl = pl->classes[c0 + i];
-          sm_gemm_prob& P = ga.p[i];
-          bf16_t* y = at<bf16_t>(ctx, cl.off_x[cur]);
-          bf16_t* bm = at<bf16_t>(ctx, cl.off_b);
-          const long long ss = (long long)cl.s * cl.s;
-          P.R = nullptr;
-          P.scale = sc ? at<float>(ctx, cl.off_inv) : nullptr;
-          P.batch = cl.count * mult;
-          if (phase == 0) {  // C[s][s] from Y: rows of Y (wide, K-contiguous) or columns of Y (tall)
-            P.A = P.B = y;
-            P.C = (c != 0.f) ? at<bf16_t>(ctx, cl.off_a) : bm;
-            P.sA = P.sB = cl.mat;
-            P.sC = ss;
-            P.M = P.N = cl.s;
-            P.K = cl.l;
-            P.lda = P.ldb = cl.cp;
-            P.ldc = cl.s;
-            P.layout = cl.wide ? 0 : 3;
-          } else {
-            P.C = at<bf16_t>(ctx, cl.off_x[cur ^ 1]);
-            P.sC = cl.mat;
-            P.M = cl.rp;
-            P.N = cl.cp;
-            P.ldc = cl.cp;
-            P.K = cl.s;
-            if (cl.wide) {  // Y'[rp][cp] = Bm[rp][rp] * Y[rp][cp]: second operand is [K][N]
-              P.A = bm;
-              P.B = y;
-              P.sA = ss;
-              P.sB = cl.mat;
-              P.lda = cl.s;
-              P.ldb = cl.cp;
-              P.layout = 2;
-            } else {        // Y'[rp][cp] = Y[rp][cp] * Bm[cp][cp]^T, Bm symmetric
-              P.A = y;
-              P.B = bm;
-              P.sA = cl.mat;
-              P.sB = ss;
-              P.lda = cl.cp;
-              P.ldb = cl.s;
-              P.layout = 0;
-            }
-          }
-        }
-        int rc = sm_launch_gemm(ctx, ga, phase == 0 ? SM_K_NS_GRAM : SM_K_NS_APPLY);
-        if (rc != SM_OK) return rc;
-        if (phase == 0 && c != 0.f) {  // Bm = c A A^T + b A + a I   (A symmetric)
-          ga.scale_pow = 0;
-          ga.alpha = c;
-          ga.gamma = b;
-          ga.diag = a;
-          for (int i = 0; i < g; ++i) {
-            ns_class& cl = pl->classes[c0 + i];
-            sm_gemm_prob& P = ga.p[i];
-            P.A = P.B = P.R = at<bf16_t>(ctx, cl.off_a);
-            P.C = at<bf16_t>(ctx, cl.off_b);
-            P.scale = nullptr;
-            P.sA = P.sB = P.sC = (long long)cl.s * cl.s;
-            P.M = P.N = P.K = cl.s;
-            P.lda = P.ldb = P.ldc = cl.s;
-            P.layout = 0;
-          }
-          rc = sm_launch_gemm(ctx, ga, SM_K_NS_GRAM);
-          if (rc != SM_OK) return rc;
-        }
-      }
+    gemm_params g;
+    g.klass = SM_K_NS_GRAM;
+    g.scale_pow = sc ? 2 : 0;
+    g.alpha = (c != 0.f) ? 1.f : b;
+    g.diag = (c != 0.f) ? 0.f : a;
+    int rc = launch_over_classes(ctx, pl, g, 1, [&](ns_class& cl, sm_gemm_prob* P) {
+      gram_of_y(cl, P[0], at<bf16_t>(ctx, cl.off_x[cur]), at<bf16_t>(ctx, (c != 0.f) ? cl.off_a : cl.off_q[0]),
+                cl.count * mult);
+      P[0].scale = sc ? at<float>(ctx, cl.off_inv) : nullptr;
+    });
+    if (rc != SM_OK) return rc;
+    if (c != 0.f) {  // Bm = c G G^T + b G + a I   (G symmetric)
+      gemm_params q;
+      q.alpha = c;
+      q.gamma = b;
+      q.diag = a;
+      rc = launch_over_classes(ctx, pl, q, 1, [&](ns_class& cl, sm_gemm_prob* P) {
+        const bf16_t* gm = at<bf16_t>(ctx, cl.off_a);
+        small_product(cl, P[0], gm, gm, at<bf16_t>(ctx, cl.off_q[0]), cl.count * mult);
+        P[0].R = gm;
+      });
+      if (rc != SM_OK) return rc;
     }
+    gemm_params ap;
+    ap.klass = SM_K_NS_APPLY;
+    ap.sym = false;
+    ap.scale_pow = sc ? 1 : 0;
+    rc = launch_over_classes(ctx, pl, ap, 1, [&](ns_class& cl, sm_gemm_prob* P) {
+      apply_to_y(cl, P[0], at<bf16_t>(ctx, cl.off_q[0]), at<bf16_t>(ctx, cl.off_x[cur]),
+                 at<bf16_t>(ctx, cl.off_x[cur ^ 1]), cl.count * mult);
+      P[0].scale = sc ? at<float>(ctx, cl.off_inv) : nullptr;
+    });
+    if (rc != SM_OK) return rc;
     cur ^= 1;
   }
   *cur_io = cur;
   return SM_OK;
+}
+
+// Short-side recurrence for the cubic iteration (c == 0).  With A_k the Gram matrix of Y_k
+// over its short side and Q_k = a I + b A_k, every Y_k is Y_0 times a polynomial in A_0, so
+// all of these commute and
+//     A_{k+1} = Q_k A_k Q_k,      Y_K = (Q_{K-1} ... Q_1 Q_0) Y_0
+// hold exactly: K steps of Alg. PolarNS cost one Gram of Y, 3 (K - 1) products of s x s
+// matrices and one apply to Y, and Y is rounded to bf16 once instead of K times.  The s x s
+// matrices are kept in IEEE half precision (all of their entries are bounded by a^K, and the
+// half-precision MFMA runs at the bf16 rate): with three more mantissa bits than bf16 their
+// rounding stays below that of Y itself, which bf16 storage of the products would not.  The
+// last product is written in bf16, the type of the apply.  Rounding
+// can leave A_k with small negative eigenvalues, which the recurrence grows by a^2 per step
+// (the step-by-step form cannot have them), so a segment covers at most SM_NS_SEGMENT steps
+// and longer iterations re-form the Gram matrix from Y between segments.
+//   Gram     : A_0 = inv^2 Y Y^T,   Q_0 = a I + b A_0                (two outputs of one GEMM)
+//   L1(k)    : T = A_k Q_k   and, for k >= 1,   P <- Q_k P           (P starts as Q_0)
+//   L2(k)    : A_{k+1} = Q_k T,     Q_{k+1} = a I + b A_{k+1}
+//   last     : P <- Q_{K-1} P;      apply: Y' = inv P Y
+constexpr int SM_NS_SEGMENT = 5;
+
+int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coeffs, bool use_scale,
+                      int* cur_io) {
+  int cur = *cur_io;
+  const float a = coeffs[0], b = coeffs[1];
+  int done = 0;
+  while (done < steps) {
+    const int kk = std::min(SM_NS_SEGMENT, steps - done);
+    const bool sc = use_scale && done == 0;
+    int qi = 0, pi = 0;           // Q_k lives in off_q[qi]
+    bool p_is_q0 = true;          // P aliases off_q[0] until the first product
+    gemm_params g;
+    g.klass = SM_K_NS_GRAM;
+    g.scale_pow = sc ? 2 : 0;
+    g.out_f16 = (kk > 1);
+    if (kk == 1) {  // only Q_0 is needed
+      g.alpha = b;
+      g.diag = a;
+    } else {
+      g.alpha = 1.f;
+      g.alpha2 = b;
+      g.diag2 = a;
+    }
+    int rc = launch_over_classes(ctx, pl, g, 1, [&](ns_class& cl, sm_gemm_prob* P) {
+      gram_of_y(cl, P[0], at<bf16_t>(ctx, cl.off_x[cur]), at<bf16_t>(ctx, kk == 1 ? cl.off_q[0] : cl.off_a),
+                cl.count * mult);
+      if (kk > 1) P[0].C2 = at<bf16_t>(ctx, cl.off_q[0]);
+      P[0].scale = sc ? at<float>(ctx, cl.off_inv) : nullptr;
+    });
+    if (rc != SM_OK) return rc;
+    auto p_ptr = [&](ns_class& cl) { return at<bf16_t>(ctx, p_is_q0 ? cl.off_q[0] : cl.off_p[pi]); };
+    auto p_next = [&](ns_class& cl) { return at<bf16_t>(ctx, p_is_q0 ? cl.off_p[0] : cl.off_p[pi ^ 1]); };
+    for (int k = 0; k + 1 < kk; ++k) {
+      const bool with_p = (k >= 1);
+      gemm_params l1;
+      l1.in_f16 = l1.out_f16 = true;
+      rc = launch_over_classes(ctx, pl, l1, with_p ? 2 : 1, [&](ns_class& cl, sm_gemm_prob* P) {
+        const bf16_t* q = at<bf16_t>(ctx, cl.off_q[qi]);
+        small_product(cl, P[0], at<bf16_t>(ctx, cl.off_a), q, at<bf16_t>(ctx, cl.off_t), cl.count * mult);
+        if (with_p) small_product(cl, P[1], q, p_ptr(cl), p_next(cl), cl.count * mult);
+      });
+      if (rc != SM_OK) return rc;
+      if (with_p) {
+        if (p_is_q0) {
+          p_is_q0 = false;
+          pi = 0;
+        } else {
+          pi ^= 1;
+        }
+      }
+      gemm_params l2;
+      l2.in_f16 = l2.out_f16 = true;
+      l2.alpha2 = b;
+      l2.diag2 = a;
+      rc = launch_over_classes(ctx, pl, l2, 1, [&](ns_class& cl, sm_gemm_prob* P) {
+        small_product(cl, P[0], at<bf16_t>(ctx, cl.off_q[qi]), at<bf16_t>(ctx, cl.off_t), at<bf16_t>(ctx, cl.off_a),
+                      cl.count * mult);
+        P[0].C2 = at<bf16_t>(ctx, cl.off_q[qi ^ 1]);
+      });
+      if (rc != SM_OK) return rc;
+      qi ^= 1;
+    }
+    if (kk > 1) {  // P <- Q_{kk-1} P
+      gemm_params lp;
+      lp.in_f16 = true;  // the last product leaves in bf16 for the apply
+      rc = launch_over_classes(ctx, pl, lp, 1, [&](ns_class& cl, sm_gemm_prob* P) {
+        small_product(cl, P[0], at<bf16_t>(ctx, cl.off_q[qi]), p_ptr(cl), p_next(cl), cl.count * mult);
+      });
+      if (rc != SM_OK) return rc;
+      if (p_is_q0) {
+        p_is_q0 = false;
+        pi = 0;
+      } else {
+        pi ^= 1;
+      }
+    }
+    gemm_params ap;
+    ap.klass = SM_K_NS_APPLY;
+    ap.sym = false;
+    ap.scale_pow = sc ? 1 : 0;
+    rc = launch_over_classes(ctx, pl, ap, 1, [&](ns_class& cl, sm_gemm_prob* P) {
+      apply_to_y(cl, P[0], p_ptr(cl), at<bf16_t>(ctx, cl.off_x[cur]), at<bf16_t>(ctx, cl.off_x[cur ^ 1]),
+                 cl.count * mult);
+      P[0].scale = sc ? at<float>(ctx, cl.off_inv) : nullptr;
+    });
+    if (rc != SM_OK) return rc;
+    cur ^= 1;
+    done += kk;
+  }
+  *cur_io = cur;
+  return SM_OK;
+}
+
+// Runs `steps` Newton-Schulz steps on every class and returns the buffer index of the result.
+// The recurrence serves the cubic with |a| <= 1.5 (the paper's a = 3/2: growth of rounding noise
+// bounded by a^(2 (SM_NS_SEGMENT - 1)) < 26); other coefficients take the step-by-step form.
+// SIGNMUON_NS_PATH=stepwise forces the latter (for comparisons).
+int run_ns(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coeffs, bool use_scale, int* cur_io) {
+  static const bool force_stepwise = [] {
+    const char* e = getenv("SIGNMUON_NS_PATH");
+    return e && strcmp(e, "stepwise") == 0;
+  }();
+  if (!force_stepwise && coeffs[2] == 0.f && fabsf(coeffs[0]) <= 1.5f && steps >= 2)
+    return run_ns_recurrence(ctx, pl, mult, steps, coeffs, use_scale, cur_io);
+  return run_ns_stepwise(ctx, pl, mult, steps, coeffs, use_scale, cur_io);
 }
 
 bool bad_coeffs(const float* c) { return !c || !isfinite(c[0]) || !isfinite(c[1]) || !isfinite(c[2]); }
@@ -286,7 +463,7 @@ int signmuon_polar_ns(signmuon_ctx* ctx, void* x, int dtype, int batch, int rows
   if (!(eps >= 0.f)) return sm_fail(ctx, SM_EINVAL, "polar_ns: eps must be >= 0");
   if (!sm_aligned(x, dtype == SM_F32 ? 4 : 2)) return sm_fail(ctx, SM_EINVAL, "polar_ns: misaligned x");
   ns_plan* pl = nullptr;
-  int rc = get_plan(ctx, 1, &rows, &cols, batch, coeffs[2] != 0.f, -1, &pl);
+  int rc = get_plan(ctx, 1, &rows, &cols, batch, -1, &pl);
   if (rc != SM_OK) return rc;
   ns_class& cl = pl->classes[0];
   rc = sm_launch_copy_in(ctx, x, dtype, batch, rows, cols, at<bf16_t>(ctx, cl.off_x[0]), cl.cp, cl.mat);
@@ -400,7 +577,7 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
       return sm_fail(ctx, SM_EINVAL, "step: counts_out needs 16-byte alignment");
   }
   ns_plan* pl = nullptr;
-  int rc = get_plan(ctx, n, s->rows, s->cols, M, s->coeffs[2] != 0.f, s->sign_fmt, &pl);
+  int rc = get_plan(ctx, n, s->rows, s->cols, M, s->sign_fmt, &pl);
   if (rc != SM_OK) return rc;
 
   // a1: momentum for every block and worker, with the bf16 working copy and the sums of squares

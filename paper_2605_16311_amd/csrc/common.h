@@ -27,7 +27,7 @@ struct signmuon_ctx {
   int device = 0;
   std::string last_error;
 
-  // one growable device arena; sub-allocated by the NS plan (see plan.hip)
+  // one growable device arena; sub-allocated by the NS plan
   void* arena = nullptr;
   size_t arena_bytes = 0;
 
@@ -39,6 +39,8 @@ struct signmuon_ctx {
   std::vector<sm_event_pair> ev_pool;        // every pair ever created
   size_t ev_used = 0;                        // pairs handed out since the last reset
   std::vector<std::pair<int, size_t>> ev_log;  // (kernel class, pool index)
+  double work_flop[SM_K_COUNT] = {};         // matrix-product flops booked by timed GEMM launches
+  double work_bytes[SM_K_COUNT] = {};        // their operand + result bytes
 };
 
 int sm_fail(signmuon_ctx* ctx, int code, const std::string& msg);
@@ -161,15 +163,19 @@ int sm_launch_sumsq(signmuon_ctx* ctx, const void* x, int dtype, long long n_per
                     float* sumsq);
 
 // ---------------------------------------------------------------- GEMM (ns_gemm.hip)
-// C[b] = alpha * scale[b]^scale_pow * (opA[b] * opB[b]^T) + gamma * R[b] + diag * I
-// opA is M x K, opB is N x K, C and R are [M][ldc]; M, N, K multiples of 64.
+// v     = alpha * scale[b]^scale_pow * (opA[b] * opB[b]^T) + gamma * R[b] + diag * I     (fp32)
+// C[b]  = rnd(v);   C2[b] = rnd(alpha2 * C[b] + diag2 * I)   (second output optional)
+// opA is M x K, opB is N x K, C, C2 and R are [M][ldc]; M, N, K multiples of 64.
+// Matrices hold 16-bit elements: bf16, or IEEE half where in_f16 (A, B) / out_f16 (C, C2, R) say
+// so; the pointer type is bf16_t either way.
 struct sm_gemm_prob {
   const bf16_t* A;
   const bf16_t* B;
   bf16_t* C;
+  bf16_t* C2;            // or null
   const bf16_t* R;       // or null
   const float* scale;    // [batch] or null
-  long long sA, sB, sC;  // batch strides in elements
+  long long sA, sB, sC;  // batch strides in elements (C, C2 and R share sC)
   int M, N, K;
   int lda, ldb, ldc;
   int batch;
@@ -184,12 +190,15 @@ struct sm_gemm_args {
   int tiles_per_xcd;
   int scale_pow;  // 0, 1 or 2
   float alpha, gamma, diag;
-  int pad_;
+  float alpha2, diag2;
+  int in_f16, out_f16;
   sm_gemm_prob p[SM_GEMM_MAX_PROB];
 };
-// One grouped launch over the problem table.  klass SM_K_NS_GRAM: A == B, layout 0 or 3, symmetric
-// output (upper triangle of tiles computed, mirrored).  klass SM_K_NS_APPLY: layout 0 or 2.
-int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, int klass);
+// One grouped launch over the problem table.  sym: every problem's output is symmetric (M == N;
+// layout 0 or 3): only the upper triangle of tiles is computed and stored mirrored.  Otherwise
+// layout 0 or 2.  Half-precision operands need sym and layout 0.  klass is the profiling class
+// the launch is booked under.
+int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, bool sym, int klass);
 
 // ---------------------------------------------------------------- power iteration (poweriter.hip)
 // sigma[b] = PowerIter(X[b], P, eps, v0[b]); X bf16 [rows][ld]; scratch: (rows + 2*cols + 4) floats per batch

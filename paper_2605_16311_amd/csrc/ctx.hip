@@ -115,6 +115,14 @@ int signmuon_profile_reset(signmuon_ctx* ctx) {
   SM_HIP(ctx, hipStreamSynchronize(ctx->stream));
   ctx->ev_used = 0;
   ctx->ev_log.clear();
+  for (int k = 0; k < SM_K_COUNT; ++k) ctx->work_flop[k] = ctx->work_bytes[k] = 0.0;
+  return SM_OK;
+}
+
+int signmuon_profile_work(signmuon_ctx* ctx, int kernel_class, double* flop, double* bytes) {
+  if (!ctx || kernel_class < 0 || kernel_class >= SM_K_COUNT) return SM_EINVAL;
+  if (flop) *flop = ctx->work_flop[kernel_class];
+  if (bytes) *bytes = ctx->work_bytes[kernel_class];
   return SM_OK;
 }
 
@@ -138,8 +146,9 @@ int signmuon_profile_read(signmuon_ctx* ctx, int kernel_class, int64_t* launches
 const char* signmuon_kernel_name(int k) {
   switch (k) {
     case SM_K_MOMENTUM: return "sm_momentum_kernel";
-    case SM_K_NS_GRAM: return "sm_ns_gemm_kernel<0,*> (Gram)";
-    case SM_K_NS_APPLY: return "sm_ns_gemm_kernel<1,*> (apply)";
+    case SM_K_NS_GRAM: return "sm_ns_gemm_kernel (Gram of Y)";
+    case SM_K_NS_APPLY: return "sm_ns_gemm_kernel (apply to Y)";
+    case SM_K_NS_SMALL: return "sm_ns_gemm_kernel (short-side recurrence)";
     case SM_K_SIGN_PACK: return "sm_sign_pack_kernel";
     case SM_K_VOTE: return "sm_vote_kernel";
     case SM_K_UPDATE: return "sm_update_kernel";

@@ -46,6 +46,8 @@ namespace sm_gemm {
 
 constexpr int BK = 64, NTH = 512;
 
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
@@ -119,9 +121,29 @@ struct operand_lane {
   }
 };
 
+// 16-bit storage <-> fp32 for either element type
+__device__ __forceinline__ unsigned pack2(float lo, float hi, bool f16) {
+  if (f16) {
+    const f16x2 v = {(_Float16)lo, (_Float16)hi};
+    return __builtin_bit_cast(unsigned, v);
+  }
+  const bf16x2 v = {(bf16_t)lo, (bf16_t)hi};
+  return __builtin_bit_cast(unsigned, v);
+}
+__device__ __forceinline__ void unpack2(unsigned w, bool f16, float& lo, float& hi) {
+  if (f16) {
+    const f16x2 v = __builtin_bit_cast(f16x2, w);
+    lo = (float)v[0];
+    hi = (float)v[1];
+  } else {
+    lo = __uint_as_float(w << 16);
+    hi = __uint_as_float(w & 0xFFFF0000u);
+  }
+}
+
 // One TS x TS tile of one problem.  The four stage arrays are the kernel's own __shared__
 // variables, passed by reference so that every access keeps its identity after inlining.
-template <int TS, bool A_MN, bool B_MN, bool SYM>
+template <int TS, bool A_MN, bool B_MN, bool SYM, bool F16>
 __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gemm_prob& P, int b, int tm, int tn,
                                           unsigned char (&sA0)[TS * 128], unsigned char (&sA1)[TS * 128],
                                           unsigned char (&sB0)[TS * 128], unsigned char (&sB1)[TS * 128]) {
@@ -138,7 +160,7 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
   // would cost more registers than the kernel has).
   int tid = threadIdx.x;
   asm volatile("" : "+v"(tid));
-  const int lane = tid & 63, wv = tid >> 6;
+  const int lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform
   const int w_m = wv & 1, w_n = wv >> 1;
 
   // ---- global -> LDS: TS/8 wave-loads per operand slice; this wave issues NLOAD of A and of B.
@@ -186,8 +208,13 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
   }
 #define MMA(set)                                                                                                \
   {                                                                                                             \
-    _Pragma("unroll") for (int i = 0; i < FM; ++i) _Pragma("unroll") for (int j = 0; j < FN; ++j) acc[i][j] =   \
-        __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);                    \
+    _Pragma("unroll") for (int i = 0; i < FM; ++i) _Pragma("unroll") for (int j = 0; j < FN; ++j) {             \
+      if (F16)                                                                                                  \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, fb[set][j]),               \
+                                                           __builtin_bit_cast(f16x8, fa[set][i]), acc[i][j], 0, 0, 0); \
+      else                                                                                                      \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);        \
+    }                                                                                                           \
   }
 #define SB() __builtin_amdgcn_sched_barrier(0)
   // wait for this wave's LDS reads and global->LDS loads, then meet the other waves
@@ -249,54 +276,78 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
     if (args.scale_pow == 2) s *= s;
   }
   const float alpha = args.alpha * s;
+  const bool of16 = args.out_f16 != 0;
   const bf16_t* __restrict__ R = P.R ? P.R + (long long)b * P.sC : nullptr;
   bf16_t* __restrict__ C = P.C + (long long)b * P.sC;
-  const int fr = lane & 31, fg = lane >> 5;
+  // a fresh opaque thread id: the store addresses are worked out here, after the K loop,
+  // instead of being carried through it in registers
+  int etid = threadIdx.x;
+  asm volatile("" : "+v"(etid));
+  const int elane = etid & 63, ewv = __builtin_amdgcn_readfirstlane(etid >> 6);  // wave-uniform
+  const int e_m = ewv & 1, e_n = ewv >> 1;
+  const int fr = elane & 31, fg = elane >> 5;
   const bool mirror = SYM && (tm != tn);
   // The tile leaves through LDS so that every global store is a 16-byte piece of a full row
   // segment (TS * 2 bytes contiguous).  The four stage arrays hold 64 tile rows each (rows of
   // TS * 2 bytes, 16-byte chunk c of row r at slot c ^ (r & (CPR - 1))).  Pass 0 stages the
   // tile as computed; pass 1 (off-diagonal tiles of a symmetric output) stages its transpose.
+  // The second output is derived from the staged (bf16) first one at read-out time.
   constexpr int RB = TS * 2, CPR = TS / 8, RPP = NTH / CPR, PASSES = TS / RPP;
   auto stage = [&](int idx) -> unsigned char* { return idx == 0 ? sA0 : idx == 1 ? sA1 : idx == 2 ? sB0 : sB1; };
+  bf16_t* __restrict__ C2 = P.C2 ? P.C2 + (long long)b * P.sC : nullptr;
+  // the output value replaces the accumulator in place (one copy of the tile in registers)
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+    const int mg = m0 + e_m * WM + i * 32 + fr;
+#pragma unroll
+    for (int jn = 0; jn < FN; ++jn) {
+#pragma unroll
+      for (int vg = 0; vg < 4; ++vg) {
+        const int ng = n0 + e_n * WN + jn * 32 + 8 * vg + 4 * fg;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float o = alpha * acc[i][jn][4 * vg + e];
+          if (mg == ng + e) o += args.diag;
+          acc[i][jn][4 * vg + e] = o;
+        }
+        if (R && mg < M && ng < N) {
+          const u32x2 rv = *reinterpret_cast<const u32x2*>(R + (long long)mg * P.ldc + ng);
+          float r4[4];
+          unpack2(rv[0], of16, r4[0], r4[1]);
+          unpack2(rv[1], of16, r4[2], r4[3]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[i][jn][4 * vg + e] += args.gamma * r4[e];
+        }
+      }
+    }
+  }
 #pragma unroll
   for (int pass = 0; pass < 2; ++pass) {
     if (pass == 1 && !mirror) break;
     if (pass == 1) __syncthreads();  // pass 0 has been read out
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
-      const int ml = w_m * WM + i * 32 + fr;  // tile row of this lane
-      const int mg = m0 + ml;
+      const int ml = e_m * WM + i * 32 + fr;  // tile row of this lane
 #pragma unroll
       for (int jn = 0; jn < FN; ++jn) {
 #pragma unroll
         for (int vg = 0; vg < 4; ++vg) {
-          const int nl = w_n * WN + jn * 32 + 8 * vg + 4 * fg;  // first of 4 tile columns
-          const int ng = n0 + nl;
-          float o[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            o[e] = alpha * acc[i][jn][4 * vg + e];
-            if (mg == ng + e) o[e] += args.diag;
-          }
-          if (R && mg < M && ng < N) {
-            const bf16x4 rv = *reinterpret_cast<const bf16x4*>(R + (long long)mg * P.ldc + ng);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] += args.gamma * (float)rv[e];
-          }
-          const bf16x4 h = {(bf16_t)o[0], (bf16_t)o[1], (bf16_t)o[2], (bf16_t)o[3]};
+          const int nl = e_n * WN + jn * 32 + 8 * vg + 4 * fg;  // first of 4 tile columns
+          const u32x2 h = {pack2(acc[i][jn][4 * vg], acc[i][jn][4 * vg + 1], of16),
+                           pack2(acc[i][jn][4 * vg + 2], acc[i][jn][4 * vg + 3], of16)};
           if (pass == 0) {
-            // rows w_m*WM + i*32 .. +31 lie in one stage array (64 rows each): uniform choice
-            unsigned char* sp = stage((w_m * WM + i * 32) >> 6);
+            // rows e_m*WM + i*32 .. +31 lie in one stage array (64 rows each): uniform choice
+            unsigned char* sp = stage((e_m * WM + i * 32) >> 6);
             const int r = ml & 63;
-            *reinterpret_cast<bf16x4*>(sp + r * RB + ((((nl >> 3) ^ (ml & (CPR - 1)))) << 4) + (nl & 7) * 2) = h;
+            *reinterpret_cast<u32x2*>(sp + r * RB + ((((nl >> 3) ^ (ml & (CPR - 1)))) << 4) + (nl & 7) * 2) = h;
           } else {
             // transposed: element (ml, nl + e) goes to row nl + e, column ml
-            unsigned char* sp = stage((w_n * WN + jn * 32) >> 6);
+            unsigned char* sp = stage((e_n * WN + jn * 32) >> 6);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               const int tr = nl + e;
-              *reinterpret_cast<bf16_t*>(sp + (tr & 63) * RB + ((((ml >> 3) ^ (tr & (CPR - 1)))) << 4) + (ml & 7) * 2) = h[e];
+              *reinterpret_cast<unsigned short*>(sp + (tr & 63) * RB + ((((ml >> 3) ^ (tr & (CPR - 1)))) << 4) + (ml & 7) * 2) =
+                  (unsigned short)(h[e >> 1] >> (16 * (e & 1)));
             }
           }
         }
@@ -304,7 +355,7 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
     }
     __syncthreads();
     // read out: thread t handles chunk t % CPR of rows t / CPR + RPP * k
-    const int rc = tid % CPR, rr = tid / CPR;
+    const int rc = etid % CPR, rr = etid / CPR;
     const int row_base = (pass == 0) ? m0 : n0, col_base = (pass == 0) ? n0 : m0;
     const int rows_lim = (pass == 0) ? M : N, cols_lim = (pass == 0) ? N : M;
 #pragma unroll
@@ -313,16 +364,33 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
       const unsigned char* sp = stage((RPP * k) >> 6);
       const u32x4 v = *reinterpret_cast<const u32x4*>(sp + (row & 63) * RB + ((rc ^ (row & (CPR - 1))) << 4));
       const int gr = row_base + row, gc = col_base + rc * 8;
-      if (gr < rows_lim && gc < cols_lim) *reinterpret_cast<u32x4*>(C + (long long)gr * P.ldc + gc) = v;
+      if (gr < rows_lim && gc < cols_lim) {
+        *reinterpret_cast<u32x4*>(C + (long long)gr * P.ldc + gc) = v;
+        if (C2) {  // second output from the rounded first one
+          u32x4 w;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            float lo, hi;
+            unpack2(v[q], of16, lo, hi);
+            lo *= args.alpha2;
+            hi *= args.alpha2;
+            if (gr == gc + 2 * q) lo += args.diag2;
+            if (gr == gc + 2 * q + 1) hi += args.diag2;
+            w[q] = pack2(lo, hi, of16);
+          }
+          *reinterpret_cast<u32x4*>(C2 + (long long)gr * P.ldc + gc) = w;
+        }
+      }
     }
   }
 }
 
-// KIND 0: Gram half-step (symmetric output; operands both KC or both MN).
-// KIND 1: apply half-step (A is KC; B is KC or MN).
+// KIND 0: symmetric output, bf16 operands both KC or both MN; the upper triangle of tiles is computed.
+// KIND 1: general output, bf16 operands (A is KC; B is KC or MN).
+// KIND 2: symmetric output, half-precision operands, both KC.
 template <int KIND, int TS>
 __global__ void __launch_bounds__(NTH) sm_ns_gemm_kernel(const sm_gemm_args args) {
-  constexpr bool SYM = (KIND == 0);
+  constexpr bool SYM = (KIND != 1);
   __shared__ __attribute__((aligned(1024))) unsigned char sA0[TS * 128], sA1[TS * 128];
   __shared__ __attribute__((aligned(1024))) unsigned char sB0[TS * 128], sB1[TS * 128];
 
@@ -359,14 +427,16 @@ __global__ void __launch_bounds__(NTH) sm_ns_gemm_kernel(const sm_gemm_args args
     }
     if (KIND == 0) {
       if (P.layout == 0)
-        gemm_tile<TS, false, false, true>(args, P, b, tm, tn, sA0, sA1, sB0, sB1);
+        gemm_tile<TS, false, false, true, false>(args, P, b, tm, tn, sA0, sA1, sB0, sB1);
       else
-        gemm_tile<TS, true, true, true>(args, P, b, tm, tn, sA0, sA1, sB0, sB1);
-    } else {
+        gemm_tile<TS, true, true, true, false>(args, P, b, tm, tn, sA0, sA1, sB0, sB1);
+    } else if (KIND == 1) {
       if (P.layout == 0)
-        gemm_tile<TS, false, false, false>(args, P, b, tm, tn, sA0, sA1, sB0, sB1);
+        gemm_tile<TS, false, false, false, false>(args, P, b, tm, tn, sA0, sA1, sB0, sB1);
       else
-        gemm_tile<TS, false, true, false>(args, P, b, tm, tn, sA0, sA1, sB0, sB1);
+        gemm_tile<TS, false, true, false, false>(args, P, b, tm, tn, sA0, sA1, sB0, sB1);
+    } else {
+      gemm_tile<TS, false, false, true, true>(args, P, b, tm, tn, sA0, sA1, sB0, sB1);
     }
   }
 }
@@ -388,17 +458,20 @@ static void fill_tiles(sm_gemm_args& args, bool sym, int ts) {
 }  // namespace sm_gemm
 using namespace sm_gemm;
 
-// Per problem, P.layout bit 0: A is MN-contiguous, bit 1: B is MN-contiguous.  klass SM_K_NS_GRAM:
-// A == B, symmetric output, layout 0 or 3.  klass SM_K_NS_APPLY: layout 0 or 2.  K multiple of 64.
-int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, int klass) {
-  const bool gram = (klass == SM_K_NS_GRAM);
+// Per problem, P.layout bit 0: A is MN-contiguous, bit 1: B is MN-contiguous.  sym: symmetric
+// output, layout 0 or 3 (A and B may differ as long as the product is symmetric).  Otherwise
+// layout 0 or 2.  K multiple of 64.
+int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, bool sym, int klass) {
+  const bool gram = sym;
   for (int i = 0; i < args.n_prob; ++i) {
     const sm_gemm_prob& P = args.p[i];
     if (P.M % 64 || P.N % 64 || P.K % 64 || P.lda % 8 || P.ldb % 8 || P.ldc % 8 || !sm_aligned(P.A, 16) ||
-        !sm_aligned(P.B, 16) || !sm_aligned(P.C, 16) || P.sA % 8 || P.sB % 8 || P.sC % 8 || (gram && P.M != P.N))
+        !sm_aligned(P.B, 16) || !sm_aligned(P.C, 16) || !sm_aligned(P.C2, 16) || P.sA % 8 || P.sB % 8 || P.sC % 8 || (gram && P.M != P.N))
       return sm_fail(ctx, SM_EINVAL, "internal: GEMM operand not padded/aligned");
     if (gram ? (P.layout != 0 && P.layout != 3) : (P.layout != 0 && P.layout != 2))
       return sm_fail(ctx, SM_EUNSUPPORTED, "internal: GEMM layout combination not built");
+    if (args.in_f16 && (!sym || P.layout != 0))
+      return sm_fail(ctx, SM_EUNSUPPORTED, "internal: half-precision GEMM operands need a symmetric K-contiguous product");
     // buffer offsets are 32-bit
     const long long a_ext = (P.layout & 1) ? (long long)P.K * P.lda : (long long)P.M * P.lda;
     const long long b_ext = (P.layout & 2) ? (long long)P.K * P.ldb : (long long)P.N * P.ldb;
@@ -426,9 +499,23 @@ int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, int klass) {
   int wgs = n_cu * (ts == 128 ? 2 : 1);
   wgs = std::min(wgs / 8, args.tiles_per_xcd) * 8;
   const dim3 grid(wgs), block(NTH);
+  if ((ctx->profiling >> klass) & 1u) {
+    for (int i = 0; i < args.n_prob; ++i) {
+      const sm_gemm_prob& P = args.p[i];
+      const double mnk = (double)P.M * P.N * P.K * P.batch;
+      ctx->work_flop[klass] += 2.0 * mnk;
+      const bool same = (P.A == P.B);
+      ctx->work_bytes[klass] += 2.0 * P.batch * ((double)P.M * P.K + (same ? 0.0 : (double)P.N * P.K) +
+                                                 (double)P.M * P.N * (1 + (P.C2 != nullptr) + (P.R != nullptr)));
+    }
+  }
   {
     sm_launch_scope sc(ctx, klass);
-    if (gram && ts == 256)
+    if (args.in_f16 && ts == 256)
+      hipLaunchKernelGGL((sm_ns_gemm_kernel<2, 256>), grid, block, 0, ctx->stream, args);
+    else if (args.in_f16)
+      hipLaunchKernelGGL((sm_ns_gemm_kernel<2, 128>), grid, block, 0, ctx->stream, args);
+    else if (gram && ts == 256)
       hipLaunchKernelGGL((sm_ns_gemm_kernel<0, 256>), grid, block, 0, ctx->stream, args);
     else if (gram)
       hipLaunchKernelGGL((sm_ns_gemm_kernel<0, 128>), grid, block, 0, ctx->stream, args);

@@ -194,7 +194,13 @@ NS_CASES = [
     (2, 256, 384, 5, "spectral", O.PAPER_COEFFS),
     (2, 384, 256, 5, "spectral", O.PAPER_COEFFS),
     (2, 128, 128, 4, "none", O.PAPER_COEFFS),
-    (2, 192, 320, 3, "fro", (2.0, -1.5, 0.5)),      # quintic polynomial
+    (2, 192, 320, 3, "fro", (2.0, -1.5, 0.5)),      # quintic polynomial (step-by-step form)
+    (2, 192, 320, 4, "fro", (1.6, -0.6, 0.0)),      # cubic with a > 3/2 (step-by-step form)
+    (2, 256, 640, 2, "fro", O.PAPER_COEFFS),        # shortest short-side recurrence
+    (2, 320, 192, 7, "fro", O.PAPER_COEFFS),        # two segments (5 + 2), tall
+    (2, 256, 640, 10, "fro", O.PAPER_COEFFS),       # two full segments, wide
+    (1, 512, 512, 10, "spectral", O.PAPER_COEFFS),  # square, near convergence
+    (2, 136, 200, 6, "fro", O.PAPER_COEFFS),        # padding + two segments (5 + 1)
 ]
 
 
