@@ -23,7 +23,8 @@ struct ns_class {
   long long mat = 0;       // rp * cp
   // arena offsets in bytes
   size_t off_x[2] = {0, 0}, off_sig = 0, off_inv = 0, off_partial = 0;
-  // s x s matrices per item: Q (two buffers), A, T, P (two buffers)
+  // s x s matrices per item.  Step-by-step form: Bm in off_q[0], G in off_a.  Recurrence: A_0 in
+  // off_q[0], later A_k in off_a / off_q[1], T in off_t, P_k in off_p[0/1].
   size_t off_q[2] = {0, 0}, off_a = 0, off_t = 0, off_p[2] = {0, 0};
   int chunks = 0;          // momentum chunks per worker
 };
@@ -138,10 +139,10 @@ int get_plan(signmuon_ctx* ctx, int n, const int* rows, const int* cols, int M, 
 
 // ---- grouped GEMM launches over the classes of a plan
 struct gemm_params {
-  float alpha = 1.f, gamma = 0.f, diag = 0.f, alpha2 = 0.f, diag2 = 0.f;
+  float alpha = 1.f, gamma = 0.f, diag = 0.f, a_diag = 0.f, b_diag = 0.f;
   int scale_pow = 0;
   bool sym = true;
-  bool in_f16 = false, out_f16 = false;
+  bool in_f16 = false, out_f16 = false, r_f16 = false;
   int klass = SM_K_NS_SMALL;
 };
 
@@ -156,16 +157,17 @@ int launch_over_classes(signmuon_ctx* ctx, ns_plan* pl, const gemm_params& gp, i
     sm_gemm_args ga;
     ga.in_f16 = gp.in_f16;
     ga.out_f16 = gp.out_f16;
+    ga.r_f16 = gp.r_f16;
+    ga.pad_ = 0;
     ga.alpha = gp.alpha;
     ga.gamma = gp.gamma;
     ga.diag = gp.diag;
-    ga.alpha2 = gp.alpha2;
-    ga.diag2 = gp.diag2;
+    ga.a_diag = gp.a_diag;
+    ga.b_diag = gp.b_diag;
     ga.scale_pow = gp.scale_pow;
     for (int i = 0; i < g; ++i) {
       sm_gemm_prob* P = &ga.p[i * per_class];
       for (int j = 0; j < per_class; ++j) {
-        P[j].C2 = nullptr;
         P[j].R = nullptr;
         P[j].scale = nullptr;
         P[j].layout = 0;
@@ -292,98 +294,103 @@ int run_ns_stepwise(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const f
 // matrices are kept in IEEE half precision (all of their entries are bounded by a^K, and the
 // half-precision MFMA runs at the bf16 rate): with three more mantissa bits than bf16 their
 // rounding stays below that of Y itself, which bf16 storage of the products would not.  The
-// last product is written in bf16, the type of the apply.  Rounding
-// can leave A_k with small negative eigenvalues, which the recurrence grows by a^2 per step
-// (the step-by-step form cannot have them), so a segment covers at most SM_NS_SEGMENT steps
-// and longer iterations re-form the Gram matrix from Y between segments.
-//   Gram     : A_0 = inv^2 Y Y^T,   Q_0 = a I + b A_0                (two outputs of one GEMM)
-//   L1(k)    : T = A_k Q_k   and, for k >= 1,   P <- Q_k P           (P starts as Q_0)
-//   L2(k)    : A_{k+1} = Q_k T,     Q_{k+1} = a I + b A_{k+1}
-//   last     : P <- Q_{K-1} P;      apply: Y' = inv P Y
+// last product is written in bf16, the type of the apply.  Q_k is never stored: a product
+// Q_k X is b (A_k + (a / b) I) X, the GEMM shifting its operand by the identity on the fly.
+// Rounding can leave A_k with small negative eigenvalues, which the recurrence grows by
+// a^2 per step (the step-by-step form cannot have them), so a segment covers at most
+// SM_NS_SEGMENT steps and longer iterations re-form the Gram matrix from Y between segments.
+//   Gram     : A_0 = inv^2 Y Y^T
+//   L1(k)    : T = Q_k A_k   and   P_{k+1} = Q_k P_k   (P_2 = Q_1 Q_0 from A_1 and A_0)
+//   L2(k)    : A_{k+1} = Q_k T
+//   last     : P_K = Q_{K-1} P_{K-1};      apply: Y' = inv P_K Y
 constexpr int SM_NS_SEGMENT = 5;
 
 int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coeffs, bool use_scale,
                       int* cur_io) {
   int cur = *cur_io;
   const float a = coeffs[0], b = coeffs[1];
+  if (b == 0.f) return SM_EINVAL;  // run_ns routes b == 0 to the step-by-step form
   int done = 0;
   while (done < steps) {
     const int kk = std::min(SM_NS_SEGMENT, steps - done);
     const bool sc = use_scale && done == 0;
-    int qi = 0, pi = 0;           // Q_k lives in off_q[qi]
-    bool p_is_q0 = true;          // P aliases off_q[0] until the first product
+    // A_k alternates between off_a and off_q[1] (A_0 stays in off_q[0] until P_2 is formed);
+    // P_k (k >= 2) alternates between off_p[0] and off_p[1]
+    int ai = 0, pi = 0;
+    auto a_ptr = [&](ns_class& cl, int which) { return at<bf16_t>(ctx, which == 0 ? cl.off_a : cl.off_q[1]); };
     gemm_params g;
     g.klass = SM_K_NS_GRAM;
     g.scale_pow = sc ? 2 : 0;
     g.out_f16 = (kk > 1);
-    if (kk == 1) {  // only Q_0 is needed
+    if (kk == 1) {  // only P_1 = Q_0 is needed, in bf16
       g.alpha = b;
       g.diag = a;
-    } else {
-      g.alpha = 1.f;
-      g.alpha2 = b;
-      g.diag2 = a;
     }
     int rc = launch_over_classes(ctx, pl, g, 1, [&](ns_class& cl, sm_gemm_prob* P) {
-      gram_of_y(cl, P[0], at<bf16_t>(ctx, cl.off_x[cur]), at<bf16_t>(ctx, kk == 1 ? cl.off_q[0] : cl.off_a),
-                cl.count * mult);
-      if (kk > 1) P[0].C2 = at<bf16_t>(ctx, cl.off_q[0]);
+      gram_of_y(cl, P[0], at<bf16_t>(ctx, cl.off_x[cur]), at<bf16_t>(ctx, cl.off_q[0]), cl.count * mult);
       P[0].scale = sc ? at<float>(ctx, cl.off_inv) : nullptr;
     });
     if (rc != SM_OK) return rc;
-    auto p_ptr = [&](ns_class& cl) { return at<bf16_t>(ctx, p_is_q0 ? cl.off_q[0] : cl.off_p[pi]); };
-    auto p_next = [&](ns_class& cl) { return at<bf16_t>(ctx, p_is_q0 ? cl.off_p[0] : cl.off_p[pi ^ 1]); };
+    // products  Q_k X = b (A_k + (a / b) I) X  over half-precision s x s matrices
+    gemm_params qx;
+    qx.alpha = b;
+    qx.a_diag = a / b;
+    qx.in_f16 = qx.out_f16 = true;
+    // first product of P: P_2 = Q_1 Q_0 = b^2 (A_1 + (a / b) I) (A_0 + (a / b) I)
+    gemm_params qq = qx;
+    qq.alpha = b * b;
+    qq.b_diag = a / b;
     for (int k = 0; k + 1 < kk; ++k) {
-      const bool with_p = (k >= 1);
-      gemm_params l1;
-      l1.in_f16 = l1.out_f16 = true;
-      rc = launch_over_classes(ctx, pl, l1, with_p ? 2 : 1, [&](ns_class& cl, sm_gemm_prob* P) {
-        const bf16_t* q = at<bf16_t>(ctx, cl.off_q[qi]);
-        small_product(cl, P[0], at<bf16_t>(ctx, cl.off_a), q, at<bf16_t>(ctx, cl.off_t), cl.count * mult);
-        if (with_p) small_product(cl, P[1], q, p_ptr(cl), p_next(cl), cl.count * mult);
+      // A_k: k == 0 in off_q[0], afterwards a_ptr(ai)
+      auto ak = [&](ns_class& cl) { return k == 0 ? at<bf16_t>(ctx, cl.off_q[0]) : a_ptr(cl, ai); };
+      const bool with_p = (k >= 2);
+      rc = launch_over_classes(ctx, pl, qx, with_p ? 2 : 1, [&](ns_class& cl, sm_gemm_prob* P) {
+        small_product(cl, P[0], ak(cl), ak(cl), at<bf16_t>(ctx, cl.off_t), cl.count * mult);
+        if (with_p)
+          small_product(cl, P[1], ak(cl), at<bf16_t>(ctx, cl.off_p[pi]), at<bf16_t>(ctx, cl.off_p[pi ^ 1]),
+                        cl.count * mult);
       });
       if (rc != SM_OK) return rc;
-      if (with_p) {
-        if (p_is_q0) {
-          p_is_q0 = false;
-          pi = 0;
-        } else {
-          pi ^= 1;
-        }
+      if (with_p) pi ^= 1;
+      if (k == 1) {  // P_2 from A_1 and A_0
+        rc = launch_over_classes(ctx, pl, qq, 1, [&](ns_class& cl, sm_gemm_prob* P) {
+          small_product(cl, P[0], ak(cl), at<bf16_t>(ctx, cl.off_q[0]), at<bf16_t>(ctx, cl.off_p[pi]), cl.count * mult);
+        });
+        if (rc != SM_OK) return rc;
       }
-      gemm_params l2;
-      l2.in_f16 = l2.out_f16 = true;
-      l2.alpha2 = b;
-      l2.diag2 = a;
-      rc = launch_over_classes(ctx, pl, l2, 1, [&](ns_class& cl, sm_gemm_prob* P) {
-        small_product(cl, P[0], at<bf16_t>(ctx, cl.off_q[qi]), at<bf16_t>(ctx, cl.off_t), at<bf16_t>(ctx, cl.off_a),
-                      cl.count * mult);
-        P[0].C2 = at<bf16_t>(ctx, cl.off_q[qi ^ 1]);
+      const int an = (k == 0) ? 0 : (ai ^ 1);
+      rc = launch_over_classes(ctx, pl, qx, 1, [&](ns_class& cl, sm_gemm_prob* P) {
+        small_product(cl, P[0], ak(cl), at<bf16_t>(ctx, cl.off_t), a_ptr(cl, an), cl.count * mult);
       });
       if (rc != SM_OK) return rc;
-      qi ^= 1;
+      ai = an;
     }
-    if (kk > 1) {  // P <- Q_{kk-1} P
-      gemm_params lp;
-      lp.in_f16 = true;  // the last product leaves in bf16 for the apply
+    int p_final = -1;  // -1: P_1 = Q_0 (bf16, in off_q[0]); else index into off_p
+    if (kk == 2) {  // P_2 = Q_1 Q_0, written in bf16 for the apply
+      gemm_params lp = qq;
+      lp.out_f16 = false;
       rc = launch_over_classes(ctx, pl, lp, 1, [&](ns_class& cl, sm_gemm_prob* P) {
-        small_product(cl, P[0], at<bf16_t>(ctx, cl.off_q[qi]), p_ptr(cl), p_next(cl), cl.count * mult);
+        small_product(cl, P[0], a_ptr(cl, ai), at<bf16_t>(ctx, cl.off_q[0]), at<bf16_t>(ctx, cl.off_p[0]), cl.count * mult);
       });
       if (rc != SM_OK) return rc;
-      if (p_is_q0) {
-        p_is_q0 = false;
-        pi = 0;
-      } else {
-        pi ^= 1;
-      }
+      p_final = 0;
+    } else if (kk > 2) {  // P_K = Q_{kk-1} P_{kk-1}
+      gemm_params lp = qx;
+      lp.out_f16 = false;
+      rc = launch_over_classes(ctx, pl, lp, 1, [&](ns_class& cl, sm_gemm_prob* P) {
+        small_product(cl, P[0], a_ptr(cl, ai), at<bf16_t>(ctx, cl.off_p[pi]), at<bf16_t>(ctx, cl.off_p[pi ^ 1]),
+                      cl.count * mult);
+      });
+      if (rc != SM_OK) return rc;
+      p_final = pi ^ 1;
     }
     gemm_params ap;
     ap.klass = SM_K_NS_APPLY;
     ap.sym = false;
     ap.scale_pow = sc ? 1 : 0;
     rc = launch_over_classes(ctx, pl, ap, 1, [&](ns_class& cl, sm_gemm_prob* P) {
-      apply_to_y(cl, P[0], p_ptr(cl), at<bf16_t>(ctx, cl.off_x[cur]), at<bf16_t>(ctx, cl.off_x[cur ^ 1]),
-                 cl.count * mult);
+      apply_to_y(cl, P[0], at<bf16_t>(ctx, p_final < 0 ? cl.off_q[0] : cl.off_p[p_final]),
+                 at<bf16_t>(ctx, cl.off_x[cur]), at<bf16_t>(ctx, cl.off_x[cur ^ 1]), cl.count * mult);
       P[0].scale = sc ? at<float>(ctx, cl.off_inv) : nullptr;
     });
     if (rc != SM_OK) return rc;
@@ -403,7 +410,7 @@ int run_ns(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coe
     const char* e = getenv("SIGNMUON_NS_PATH");
     return e && strcmp(e, "stepwise") == 0;
   }();
-  if (!force_stepwise && coeffs[2] == 0.f && fabsf(coeffs[0]) <= 1.5f && steps >= 2)
+  if (!force_stepwise && coeffs[2] == 0.f && coeffs[1] != 0.f && fabsf(coeffs[0]) <= 1.5f && steps >= 2)
     return run_ns_recurrence(ctx, pl, mult, steps, coeffs, use_scale, cur_io);
   return run_ns_stepwise(ctx, pl, mult, steps, coeffs, use_scale, cur_io);
 }

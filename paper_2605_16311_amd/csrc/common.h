@@ -163,19 +163,20 @@ int sm_launch_sumsq(signmuon_ctx* ctx, const void* x, int dtype, long long n_per
                     float* sumsq);
 
 // ---------------------------------------------------------------- GEMM (ns_gemm.hip)
-// v     = alpha * scale[b]^scale_pow * (opA[b] * opB[b]^T) + gamma * R[b] + diag * I     (fp32)
-// C[b]  = rnd(v);   C2[b] = rnd(alpha2 * C[b] + diag2 * I)   (second output optional)
-// opA is M x K, opB is N x K, C, C2 and R are [M][ldc]; M, N, K multiples of 64.
-// Matrices hold 16-bit elements: bf16, or IEEE half where in_f16 (A, B) / out_f16 (C, C2, R) say
-// so; the pointer type is bf16_t either way.
+// C[b] = rnd(rnd(alpha * scale[b]^scale_pow * (A' * B'^T) + diag * I) + gamma * R[b]),
+//        A' = opA[b] + a_diag I,  B' = opB[b] + b_diag I
+// opA is M x K, opB is N x K, C and R are [M][ldc]; M, N, K multiples of 64; fp32 accumulation.
+// With a symmetric output R must be symmetric too.  The identity shifts need half-precision
+// K-contiguous operands.
+// Matrices hold 16-bit elements: bf16, or IEEE half where in_f16 (A, B) / out_f16 (C) say
+// so (r_f16 for R); the pointer type is bf16_t either way.
 struct sm_gemm_prob {
   const bf16_t* A;
   const bf16_t* B;
   bf16_t* C;
-  bf16_t* C2;            // or null
   const bf16_t* R;       // or null
   const float* scale;    // [batch] or null
-  long long sA, sB, sC;  // batch strides in elements (C, C2 and R share sC)
+  long long sA, sB, sC;  // batch strides in elements (C and R share sC)
   int M, N, K;
   int lda, ldb, ldc;
   int batch;
@@ -190,8 +191,9 @@ struct sm_gemm_args {
   int tiles_per_xcd;
   int scale_pow;  // 0, 1 or 2
   float alpha, gamma, diag;
-  float alpha2, diag2;
-  int in_f16, out_f16;
+  float a_diag, b_diag;  // 0 = none
+  int in_f16, out_f16, r_f16;
+  int pad_;
   sm_gemm_prob p[SM_GEMM_MAX_PROB];
 };
 // One grouped launch over the problem table.  sym: every problem's output is symmetric (M == N;

@@ -247,12 +247,38 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
     SB();                                                                 \
     SYNC();                                                               \
     ++j;                                                                  \
+    if (j < nk) SHIFT_DIAG(na, nb, j);                                    \
   }
 
+  // Optional identity shift of the operands, opA + a_diag I and opB + b_diag I (half precision,
+  // K-contiguous): the diagonal crosses a slice only inside the tile's own row (column) range, and
+  // there one wave per operand adds the shift to the 64 diagonal elements of the slice in LDS,
+  // after the slice has landed and before any fragment of it is read.
+  const _Float16 dga = (_Float16)args.a_diag, dgb = (_Float16)args.b_diag;
+  const bool dg_a = F16 && args.a_diag != 0.f, dg_b = F16 && args.b_diag != 0.f;
+#define SHIFT_DIAG(sa, sb, slice)                                                                      \
+  if (F16 && (dg_a || dg_b)) {                                                                         \
+    const int ra = (slice) * BK - m0, rb = (slice) * BK - n0; /* tile row of the slice's first k */   \
+    const bool ha = dg_a && ra >= 0 && ra < TS, hb = dg_b && rb >= 0 && rb < TS;                       \
+    if (ha || hb) {                                                                                    \
+      if (wv == 0 && ha) {                                                                             \
+        const int r = ra + lane;                                                                       \
+        _Float16* e = reinterpret_cast<_Float16*>((sa) + r * (BK * 2) + (((lane >> 3) ^ ((r >> 1) & 7)) << 4)) + (lane & 7); \
+        *e = (_Float16)(*e + dga);                                                                     \
+      }                                                                                                \
+      if (wv == 1 && hb) {                                                                             \
+        const int r = rb + lane;                                                                       \
+        _Float16* e = reinterpret_cast<_Float16*>((sb) + r * (BK * 2) + (((lane >> 3) ^ ((r >> 1) & 7)) << 4)) + (lane & 7); \
+        *e = (_Float16)(*e + dgb);                                                                     \
+      }                                                                                                \
+      __syncthreads();                                                                                 \
+    }                                                                                                  \
+  }
   const int nk = K / BK;
   int j = 0;
   ISSUE(sA0, sB0, 0);
   SYNC();
+  SHIFT_DIAG(sA0, sB0, 0);
   // first slice: no pending k-step from a previous slice
   SLICE_STEP(sA0, sB0, sA1, sB1, true);
   // Past the end the issue re-reads the last slice (never consumed), so every step has the same shape.
@@ -263,6 +289,7 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
   if (j < nk) SLICE_STEP(sA1, sB1, sA0, sB0, false);
   MMA(1);  // k-step 3 of the last slice
 #undef SLICE_STEP
+#undef SHIFT_DIAG
 #undef SYNC
 #undef SB
 #undef FETCH
@@ -277,7 +304,6 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
   }
   const float alpha = args.alpha * s;
   const bool of16 = args.out_f16 != 0;
-  const bf16_t* __restrict__ R = P.R ? P.R + (long long)b * P.sC : nullptr;
   bf16_t* __restrict__ C = P.C + (long long)b * P.sC;
   // a fresh opaque thread id: the store addresses are worked out here, after the K loop,
   // instead of being carried through it in registers
@@ -287,99 +313,96 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
   const int e_m = ewv & 1, e_n = ewv >> 1;
   const int fr = elane & 31, fg = elane >> 5;
   const bool mirror = SYM && (tm != tn);
-  // The tile leaves through LDS so that every global store is a 16-byte piece of a full row
-  // segment (TS * 2 bytes contiguous).  The four stage arrays hold 64 tile rows each (rows of
-  // TS * 2 bytes, 16-byte chunk c of row r at slot c ^ (r & (CPR - 1))).  Pass 0 stages the
-  // tile as computed; pass 1 (off-diagonal tiles of a symmetric output) stages its transpose.
-  // The second output is derived from the staged (bf16) first one at read-out time.
+  // The tile leaves through LDS so that every global store is a 16-byte piece of a row.  The four
+  // stage arrays hold 64 tile rows each (rows of TS * 2 bytes, 16-byte chunk c of row r at slot
+  // c ^ (r & (CPR - 1))).  The tile is staged once; it is read out row by row for C and, for an
+  // off-diagonal tile of a symmetric output, once more column by column (transposing LDS reads)
+  // for the mirrored tile.  The R term (a symmetric matrix when the output is) is added at
+  // read-out, on the rounded product, with loads shaped like the stores.
   constexpr int RB = TS * 2, CPR = TS / 8, RPP = NTH / CPR, PASSES = TS / RPP;
+  const bf16_t* __restrict__ R = P.R ? P.R + (long long)b * P.sC : nullptr;
+  const bool rf16 = args.r_f16 != 0;
+  const float gamma = args.gamma;
+  // 8 staged outputs + gamma R at element offset off, rounded again
+  auto add_r = [&](u32x4 v, const bf16_t* r, long long off) -> u32x4 {
+    const u32x4 a = *reinterpret_cast<const u32x4*>(r + off);
+    u32x4 w;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float lo, hi, alo, ahi;
+      unpack2(v[q], of16, lo, hi);
+      unpack2(a[q], rf16, alo, ahi);
+      lo += gamma * alo;
+      hi += gamma * ahi;
+      w[q] = pack2(lo, hi, of16);
+    }
+    return w;
+  };
   auto stage = [&](int idx) -> unsigned char* { return idx == 0 ? sA0 : idx == 1 ? sA1 : idx == 2 ? sB0 : sB1; };
-  bf16_t* __restrict__ C2 = P.C2 ? P.C2 + (long long)b * P.sC : nullptr;
-  // the output value replaces the accumulator in place (one copy of the tile in registers)
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
-    const int mg = m0 + e_m * WM + i * 32 + fr;
+    const int ml = e_m * WM + i * 32 + fr;  // tile row of this lane
+    const int mg = m0 + ml;
+    // rows e_m*WM + i*32 .. +31 lie in one stage array (64 rows each): uniform choice
+    unsigned char* sp = stage((e_m * WM + i * 32) >> 6);
 #pragma unroll
     for (int jn = 0; jn < FN; ++jn) {
 #pragma unroll
       for (int vg = 0; vg < 4; ++vg) {
-        const int ng = n0 + e_n * WN + jn * 32 + 8 * vg + 4 * fg;
+        const int nl = e_n * WN + jn * 32 + 8 * vg + 4 * fg;  // first of 4 tile columns
+        const int ng = n0 + nl;
+        float o[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          float o = alpha * acc[i][jn][4 * vg + e];
-          if (mg == ng + e) o += args.diag;
-          acc[i][jn][4 * vg + e] = o;
+          o[e] = alpha * acc[i][jn][4 * vg + e];
+          if (mg == ng + e) o[e] += args.diag;
         }
-        if (R && mg < M && ng < N) {
-          const u32x2 rv = *reinterpret_cast<const u32x2*>(R + (long long)mg * P.ldc + ng);
-          float r4[4];
-          unpack2(rv[0], of16, r4[0], r4[1]);
-          unpack2(rv[1], of16, r4[2], r4[3]);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) acc[i][jn][4 * vg + e] += args.gamma * r4[e];
-        }
+        const u32x2 h = {pack2(o[0], o[1], of16), pack2(o[2], o[3], of16)};
+        *reinterpret_cast<u32x2*>(sp + (ml & 63) * RB + ((((nl >> 3) ^ (ml & (CPR - 1)))) << 4) + (nl & 7) * 2) = h;
       }
     }
   }
-#pragma unroll
-  for (int pass = 0; pass < 2; ++pass) {
-    if (pass == 1 && !mirror) break;
-    if (pass == 1) __syncthreads();  // pass 0 has been read out
-#pragma unroll
-    for (int i = 0; i < FM; ++i) {
-      const int ml = e_m * WM + i * 32 + fr;  // tile row of this lane
-#pragma unroll
-      for (int jn = 0; jn < FN; ++jn) {
-#pragma unroll
-        for (int vg = 0; vg < 4; ++vg) {
-          const int nl = e_n * WN + jn * 32 + 8 * vg + 4 * fg;  // first of 4 tile columns
-          const u32x2 h = {pack2(acc[i][jn][4 * vg], acc[i][jn][4 * vg + 1], of16),
-                           pack2(acc[i][jn][4 * vg + 2], acc[i][jn][4 * vg + 3], of16)};
-          if (pass == 0) {
-            // rows e_m*WM + i*32 .. +31 lie in one stage array (64 rows each): uniform choice
-            unsigned char* sp = stage((e_m * WM + i * 32) >> 6);
-            const int r = ml & 63;
-            *reinterpret_cast<u32x2*>(sp + r * RB + ((((nl >> 3) ^ (ml & (CPR - 1)))) << 4) + (nl & 7) * 2) = h;
-          } else {
-            // transposed: element (ml, nl + e) goes to row nl + e, column ml
-            unsigned char* sp = stage((e_n * WN + jn * 32) >> 6);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const int tr = nl + e;
-              *reinterpret_cast<unsigned short*>(sp + (tr & 63) * RB + ((((ml >> 3) ^ (tr & (CPR - 1)))) << 4) + (ml & 7) * 2) =
-                  (unsigned short)(h[e >> 1] >> (16 * (e & 1)));
-            }
-          }
-        }
-      }
-    }
-    __syncthreads();
-    // read out: thread t handles chunk t % CPR of rows t / CPR + RPP * k
+  __syncthreads();
+  {
+    // rows: thread t handles chunk t % CPR of rows t / CPR + RPP * k
     const int rc = etid % CPR, rr = etid / CPR;
-    const int row_base = (pass == 0) ? m0 : n0, col_base = (pass == 0) ? n0 : m0;
-    const int rows_lim = (pass == 0) ? M : N, cols_lim = (pass == 0) ? N : M;
 #pragma unroll
     for (int k = 0; k < PASSES; ++k) {
       const int row = rr + RPP * k;  // tile row; (row >> 6) == (RPP * k) >> 6 is a constant
       const unsigned char* sp = stage((RPP * k) >> 6);
       const u32x4 v = *reinterpret_cast<const u32x4*>(sp + (row & 63) * RB + ((rc ^ (row & (CPR - 1))) << 4));
-      const int gr = row_base + row, gc = col_base + rc * 8;
-      if (gr < rows_lim && gc < cols_lim) {
-        *reinterpret_cast<u32x4*>(C + (long long)gr * P.ldc + gc) = v;
-        if (C2) {  // second output from the rounded first one
-          u32x4 w;
+      const int gr = m0 + row, gc = n0 + rc * 8;
+      if (gr < M && gc < N) {
+        const long long off = (long long)gr * P.ldc + gc;
+        *reinterpret_cast<u32x4*>(C + off) = R ? add_r(v, R, off) : v;
+      }
+    }
+  }
+  if (mirror) {
+    // columns: a 16-lane group reads 8 tile rows x 16 tile columns with two transposing reads (lane i
+    // addresses row i / 4, 8-byte segment i % 4 of a 4 x 16 block and receives column i), which
+    // leaves lane i with 8 consecutive elements of row (column block + i) of the mirrored tile.
+    // The four groups of a wave take neighbouring row chunks, i.e. 64 contiguous bytes per row.
+    constexpr int NRC = TS / 8;         // 8-row chunks in the tile
+    constexpr int CPI = 32 / NRC;       // 16-column blocks covered per iteration by the 32 groups
+    const int G = etid >> 4, i16 = etid & 15;
+    const int rchunk = G % NRC;
+    const unsigned char* sp = stage((8 * (ewv * 4 % NRC)) >> 6);  // (8 * rchunk) >> 6 is wave-uniform
+    const int r0 = 8 * rchunk + (i16 >> 2);
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            float lo, hi;
-            unpack2(v[q], of16, lo, hi);
-            lo *= args.alpha2;
-            hi *= args.alpha2;
-            if (gr == gc + 2 * q) lo += args.diag2;
-            if (gr == gc + 2 * q + 1) hi += args.diag2;
-            w[q] = pack2(lo, hi, of16);
-          }
-          *reinterpret_cast<u32x4*>(C2 + (long long)gr * P.ldc + gc) = w;
-        }
+    for (int k = 0; k < (TS / 16) / CPI; ++k) {
+      const int cb = 16 * (CPI * k + G / NRC);
+      const int col = cb + 4 * (i16 & 3);
+      const unsigned char* p0 = sp + (r0 & 63) * RB + ((((col >> 3) ^ (r0 & (CPR - 1)))) << 4) + (col & 7) * 2;
+      const unsigned char* p1 = sp + ((r0 + 4) & 63) * RB + ((((col >> 3) ^ ((r0 + 4) & (CPR - 1)))) << 4) + (col & 7) * 2;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p0));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p1));
+      const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      const int gr = n0 + cb + i16, gc = m0 + 8 * rchunk;
+      if (gr < N && gc < M) {
+        const long long off = (long long)gr * P.ldc + gc;
+        const u32x4 vv = __builtin_bit_cast(u32x4, v);
+        *reinterpret_cast<u32x4*>(C + off) = R ? add_r(vv, R, off) : vv;
       }
     }
   }
@@ -466,10 +489,13 @@ int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, bool sym, int klass) {
   for (int i = 0; i < args.n_prob; ++i) {
     const sm_gemm_prob& P = args.p[i];
     if (P.M % 64 || P.N % 64 || P.K % 64 || P.lda % 8 || P.ldb % 8 || P.ldc % 8 || !sm_aligned(P.A, 16) ||
-        !sm_aligned(P.B, 16) || !sm_aligned(P.C, 16) || !sm_aligned(P.C2, 16) || P.sA % 8 || P.sB % 8 || P.sC % 8 || (gram && P.M != P.N))
+        !sm_aligned(P.B, 16) || !sm_aligned(P.C, 16) || P.sA % 8 || P.sB % 8 || P.sC % 8 || (gram && P.M != P.N))
       return sm_fail(ctx, SM_EINVAL, "internal: GEMM operand not padded/aligned");
     if (gram ? (P.layout != 0 && P.layout != 3) : (P.layout != 0 && P.layout != 2))
       return sm_fail(ctx, SM_EUNSUPPORTED, "internal: GEMM layout combination not built");
+    if (!sm_aligned(P.R, 16)) return sm_fail(ctx, SM_EINVAL, "internal: GEMM R term misaligned");
+    if ((args.a_diag != 0.f || args.b_diag != 0.f) && !args.in_f16)
+      return sm_fail(ctx, SM_EUNSUPPORTED, "internal: operand identity shift needs half-precision operands");
     if (args.in_f16 && (!sym || P.layout != 0))
       return sm_fail(ctx, SM_EUNSUPPORTED, "internal: half-precision GEMM operands need a symmetric K-contiguous product");
     // buffer offsets are 32-bit
@@ -506,7 +532,7 @@ int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, bool sym, int klass) {
       ctx->work_flop[klass] += 2.0 * mnk;
       const bool same = (P.A == P.B);
       ctx->work_bytes[klass] += 2.0 * P.batch * ((double)P.M * P.K + (same ? 0.0 : (double)P.N * P.K) +
-                                                 (double)P.M * P.N * (1 + (P.C2 != nullptr) + (P.R != nullptr)));
+                                                 (double)P.M * P.N * (1 + (P.R != nullptr && P.R != P.A && P.R != P.B)));
     }
   }
   {
