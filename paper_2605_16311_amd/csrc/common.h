@@ -188,8 +188,8 @@ constexpr int SM_GEMM_MAX_PROB = 32;
 struct sm_gemm_args {
   int n_prob;
   int total_tiles;
-  int tiles_per_xcd;
-  int scale_pow;  // 0, 1 or 2
+  int xcd_begin[9];  // XCD x owns tiles [xcd_begin[x], xcd_begin[x + 1]) of the tile list
+  int scale_pow;     // 0, 1 or 2
   float alpha, gamma, diag;
   float a_diag, b_diag;  // 0 = none
   int in_f16, out_f16, r_f16;

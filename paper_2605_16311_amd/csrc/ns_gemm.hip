@@ -419,14 +419,14 @@ __global__ void __launch_bounds__(NTH) sm_ns_gemm_kernel(const sm_gemm_args args
 
   // Persistent workgroups: the grid is one (TS = 256) or two (TS = 128) workgroups per CU and each
   // walks a list of tiles, so the global stores of one tile drain while the next tile is loaded
-  // and multiplied.  Workgroup ids are dealt round-robin to the 8 XCDs: XCD x owns the contiguous
-  // eighth [x * tiles_per_xcd, (x + 1) * tiles_per_xcd) of the tile list and its workgroups take
-  // neighbouring tiles at any one time, so tiles that share operand panels share an L2.
+  // and multiplied.  Workgroup ids are dealt round-robin to the 8 XCDs: XCD x owns a contiguous
+  // range of the tile list (ranges of equal estimated cost) and its workgroups take neighbouring
+  // tiles at any one time, so tiles that share operand panels share an L2.
   const int wg = blockIdx.x;
   const int per_xcd_wgs = gridDim.x >> 3;
-  const int xcd_end = min((int)(((wg & 7) + 1) * args.tiles_per_xcd), args.total_tiles);
+  const int xcd_end = args.xcd_begin[(wg & 7) + 1];
   bool first_tile = true;
-  for (int L = (wg & 7) * args.tiles_per_xcd + (wg >> 3); L < xcd_end; L += per_xcd_wgs) {
+  for (int L = args.xcd_begin[wg & 7] + (wg >> 3); L < xcd_end; L += per_xcd_wgs) {
     if (!first_tile) __syncthreads();  // the previous tile has been read out of the stage arrays
     first_tile = false;
     int pi = 0;
@@ -464,18 +464,44 @@ __global__ void __launch_bounds__(NTH) sm_ns_gemm_kernel(const sm_gemm_args args
   }
 }
 
-// tile bookkeeping shared by every instantiation
-static void fill_tiles(sm_gemm_args& args, bool sym, int ts) {
+// Tile bookkeeping shared by every instantiation.  A tile costs its K slices plus a fixed part
+// (prologue and write-out, about six slices' worth); the list is cut into eight ranges of equal
+// cost, one per XCD.  Returns the largest number of tiles any XCD owns.
+static int fill_tiles(sm_gemm_args& args, bool sym, int ts) {
+  constexpr double FIXED = 6.0;
   int total = 0;
+  double cost = 0.0;
   for (int i = 0; i < args.n_prob; ++i) {
     sm_gemm_prob& P = args.p[i];
     P.tiles_m = (P.M + ts - 1) / ts;
     P.tiles_n = (P.N + ts - 1) / ts;
     P.tile_begin = total;
-    total += (sym ? P.tiles_m * (P.tiles_m + 1) / 2 : P.tiles_m * P.tiles_n) * P.batch;
+    const int n = (sym ? P.tiles_m * (P.tiles_m + 1) / 2 : P.tiles_m * P.tiles_n) * P.batch;
+    total += n;
+    cost += n * (P.K / 64 + FIXED);
   }
   args.total_tiles = total;
-  args.tiles_per_xcd = (total + 7) / 8;
+  args.xcd_begin[0] = 0;
+  int pi = 0, x = 1;
+  double done = 0.0;  // cost of the problems before pi
+  while (x < 8 && pi < args.n_prob) {
+    const sm_gemm_prob& P = args.p[pi];
+    const int end = (pi + 1 < args.n_prob) ? args.p[pi + 1].tile_begin : total;
+    const double per_tile = P.K / 64 + FIXED, target = cost * x / 8;
+    const double here = done + (double)(end - P.tile_begin) * per_tile;
+    if (here < target) {
+      done = here;
+      ++pi;
+      continue;
+    }
+    int cut = P.tile_begin + (int)((target - done) / per_tile + 0.5);
+    cut = std::min(std::max(cut, args.xcd_begin[x - 1]), end);
+    args.xcd_begin[x++] = cut;
+  }
+  for (; x <= 8; ++x) args.xcd_begin[x] = total;
+  int most = 0;
+  for (int k = 0; k < 8; ++k) most = std::max(most, args.xcd_begin[k + 1] - args.xcd_begin[k]);
+  return most;
 }
 
 }  // namespace sm_gemm
@@ -514,7 +540,7 @@ int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, bool sym, int klass) {
     fill_tiles(args, gram, 256);
     ts = (args.total_tiles >= 1024) ? 256 : 128;
   }
-  fill_tiles(args, gram, ts);
+  const int most = fill_tiles(args, gram, ts);
   if (args.total_tiles == 0) return SM_OK;
   // persistent grid: one workgroup per CU (two for the small tile), a multiple of 8, never more than tiles
   static const int n_cu = [] {
@@ -523,7 +549,7 @@ int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, bool sym, int klass) {
     return n;
   }();
   int wgs = n_cu * (ts == 128 ? 2 : 1);
-  wgs = std::min(wgs / 8, args.tiles_per_xcd) * 8;
+  wgs = std::min(wgs / 8, most) * 8;
   const dim3 grid(wgs), block(NTH);
   if ((ctx->profiling >> klass) & 1u) {
     for (int i = 0; i < args.n_prob; ++i) {
