@@ -27,6 +27,10 @@ struct ns_class {
   // off_q[0], later A_k in off_a / off_q[1], T in off_t, P_k in off_p[0/1].
   size_t off_q[2] = {0, 0}, off_a = 0, off_t = 0, off_p[2] = {0, 0};
   int chunks = 0;          // momentum chunks per worker
+  // internal sign buffers of the class: [block][worker] rows of sign_stride bytes
+  size_t off_signs = 0;
+  long long sign_stride = 0;
+  bool fuse_signs = false;  // the last apply of the pre-vote iteration can write the signs itself
 };
 
 struct ns_plan {
@@ -119,10 +123,17 @@ int get_plan(signmuon_ctx* ctx, int n, const int* rows, const int* cols, int M, 
   pl->off_pi = take((size_t)max_pi * 4);
   pl->off_signs.resize(n);
   pl->sign_stride.resize(n);
+  for (auto& c : pl->classes) {
+    const long long d = (long long)c.rows * c.cols;
+    c.sign_stride = (sign_fmt == SM_SIGN_INT8) ? sm_round_up(d, 16) : 8 * ((d + 63) / 64);
+    c.off_signs = (sign_fmt < 0) ? 0 : take((size_t)c.sign_stride * M * c.count);
+    // whole 32-bit words per 32 columns and no tail bits: the GEMM can emit the packed signs
+    c.fuse_signs = sign_fmt >= 0 && c.cols % 32 == 0 && d % 64 == 0;
+  }
   for (int i = 0; i < n; ++i) {
-    const long long d = (long long)rows[i] * cols[i];
-    pl->sign_stride[i] = (sign_fmt == SM_SIGN_INT8) ? sm_round_up(d, 16) : 8 * ((d + 63) / 64);
-    pl->off_signs[i] = (sign_fmt < 0) ? 0 : take((size_t)pl->sign_stride[i] * M);
+    const ns_class& c = pl->classes[pl->class_of[i]];
+    pl->sign_stride[i] = c.sign_stride;
+    pl->off_signs[i] = c.off_signs + (size_t)pl->index_in_class[i] * M * c.sign_stride;
   }
   pl->total = off;
   int rc = sm_arena_reserve(ctx, pl->total);
@@ -171,6 +182,9 @@ int launch_over_classes(signmuon_ctx* ctx, ns_plan* pl, const gemm_params& gp, i
         P[j].R = nullptr;
         P[j].scale = nullptr;
         P[j].layout = 0;
+        P[j].sign_out = nullptr;
+        P[j].sign_stride = 0;
+        P[j].sign_rows = P[j].sign_cols = P[j].sign_fmt = P[j].pad_ = 0;
       }
       fill(pl->classes[c0 + i], P);
     }
@@ -196,8 +210,24 @@ void gram_of_y(ns_class& cl, sm_gemm_prob& P, const bf16_t* y, bf16_t* c, int ba
 }
 
 // Y'[rp][cp] = S Y (rows <= cols; second operand stored [K][N]) or Y S, S symmetric s x s.
-void apply_to_y(ns_class& cl, sm_gemm_prob& P, const bf16_t* sm, const bf16_t* y, bf16_t* yout, int batch) {
+// signs: also (or, without write_y, only) emit the packed signs of the result into the class's
+// sign buffers.
+struct ns_sign_req {
+  int fmt;
+  bool write_y;
+};
+
+void apply_to_y(signmuon_ctx* ctx, ns_class& cl, sm_gemm_prob& P, const bf16_t* sm, const bf16_t* y, bf16_t* yout,
+                int batch, const ns_sign_req* signs) {
   const long long ss = (long long)cl.s * cl.s;
+  if (signs && cl.fuse_signs) {
+    P.sign_out = at<void>(ctx, cl.off_signs);
+    P.sign_stride = cl.sign_stride;
+    P.sign_rows = cl.rows;
+    P.sign_cols = cl.cols;
+    P.sign_fmt = signs->fmt;
+    if (!signs->write_y) yout = nullptr;
+  }
   P.C = yout;
   P.sC = cl.mat;
   P.M = cl.rp;
@@ -241,7 +271,7 @@ void small_product(ns_class& cl, sm_gemm_prob& P, const bf16_t* a, const bf16_t*
 // classes; batch = count * mult per class, starting from buffer `cur` (0/1) of each class.
 // The first step carries the per-item 1 / sigma when use_scale.  Y is read in place.
 int run_ns_stepwise(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coeffs, bool use_scale,
-                    int* cur_io) {
+                    int* cur_io, const ns_sign_req* signs) {
   int cur = *cur_io;
   const float a = coeffs[0], b = coeffs[1], c = coeffs[2];
   for (int k = 0; k < steps; ++k) {
@@ -274,8 +304,8 @@ int run_ns_stepwise(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const f
     ap.sym = false;
     ap.scale_pow = sc ? 1 : 0;
     rc = launch_over_classes(ctx, pl, ap, 1, [&](ns_class& cl, sm_gemm_prob* P) {
-      apply_to_y(cl, P[0], at<bf16_t>(ctx, cl.off_q[0]), at<bf16_t>(ctx, cl.off_x[cur]),
-                 at<bf16_t>(ctx, cl.off_x[cur ^ 1]), cl.count * mult);
+      apply_to_y(ctx, cl, P[0], at<bf16_t>(ctx, cl.off_q[0]), at<bf16_t>(ctx, cl.off_x[cur]),
+                 at<bf16_t>(ctx, cl.off_x[cur ^ 1]), cl.count * mult, (k + 1 == steps) ? signs : nullptr);
       P[0].scale = sc ? at<float>(ctx, cl.off_inv) : nullptr;
     });
     if (rc != SM_OK) return rc;
@@ -306,7 +336,7 @@ int run_ns_stepwise(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const f
 constexpr int SM_NS_SEGMENT = 5;
 
 int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coeffs, bool use_scale,
-                      int* cur_io) {
+                      int* cur_io, const ns_sign_req* signs) {
   int cur = *cur_io;
   const float a = coeffs[0], b = coeffs[1];
   if (b == 0.f) return SM_EINVAL;  // run_ns routes b == 0 to the step-by-step form
@@ -389,8 +419,9 @@ int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const
     ap.sym = false;
     ap.scale_pow = sc ? 1 : 0;
     rc = launch_over_classes(ctx, pl, ap, 1, [&](ns_class& cl, sm_gemm_prob* P) {
-      apply_to_y(cl, P[0], at<bf16_t>(ctx, p_final < 0 ? cl.off_q[0] : cl.off_p[p_final]),
-                 at<bf16_t>(ctx, cl.off_x[cur]), at<bf16_t>(ctx, cl.off_x[cur ^ 1]), cl.count * mult);
+      apply_to_y(ctx, cl, P[0], at<bf16_t>(ctx, p_final < 0 ? cl.off_q[0] : cl.off_p[p_final]),
+                 at<bf16_t>(ctx, cl.off_x[cur]), at<bf16_t>(ctx, cl.off_x[cur ^ 1]), cl.count * mult,
+                 (done + kk == steps) ? signs : nullptr);
       P[0].scale = sc ? at<float>(ctx, cl.off_inv) : nullptr;
     });
     if (rc != SM_OK) return rc;
@@ -405,14 +436,16 @@ int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const
 // The recurrence serves the cubic with |a| <= 1.5 (the paper's a = 3/2: growth of rounding noise
 // bounded by a^(2 (SM_NS_SEGMENT - 1)) < 26); other coefficients take the step-by-step form.
 // SIGNMUON_NS_PATH=stepwise forces the latter (for comparisons).
-int run_ns(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coeffs, bool use_scale, int* cur_io) {
+// signs (optional): the last apply also emits the packed signs of the classes marked fuse_signs.
+int run_ns(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coeffs, bool use_scale, int* cur_io,
+           const ns_sign_req* signs = nullptr) {
   static const bool force_stepwise = [] {
     const char* e = getenv("SIGNMUON_NS_PATH");
     return e && strcmp(e, "stepwise") == 0;
   }();
   if (!force_stepwise && coeffs[2] == 0.f && coeffs[1] != 0.f && fabsf(coeffs[0]) <= 1.5f && steps >= 2)
-    return run_ns_recurrence(ctx, pl, mult, steps, coeffs, use_scale, cur_io);
-  return run_ns_stepwise(ctx, pl, mult, steps, coeffs, use_scale, cur_io);
+    return run_ns_recurrence(ctx, pl, mult, steps, coeffs, use_scale, cur_io, signs);
+  return run_ns_stepwise(ctx, pl, mult, steps, coeffs, use_scale, cur_io, signs);
 }
 
 bool bad_coeffs(const float* c) { return !c || !isfinite(c[0]) || !isfinite(c[1]) || !isfinite(c[2]); }
@@ -638,14 +671,23 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
   }
 
   // a3 + a4: K Newton-Schulz steps on all (block, worker) matrices
+  // When the iteration has at least one step, its last apply writes the packed signs (a5) of
+  // every class whose rows pack into whole words; U itself is then only written if a tap asks.
+  ns_sign_req sreq;
+  sreq.fmt = s->sign_fmt;
+  sreq.write_y = false;
+  if (s->u_out)
+    for (int i = 0; i < n; ++i) sreq.write_y = sreq.write_y || (s->u_out[i] != nullptr);
+  const bool fused = s->ns_steps > 0;
   int cur = 0;
-  rc = run_ns(ctx, pl, M, s->ns_steps, s->coeffs, use_scale, &cur);
+  rc = run_ns(ctx, pl, M, s->ns_steps, s->coeffs, use_scale, &cur, fused ? &sreq : nullptr);
   if (rc != SM_OK) return rc;
 
   const int Kp = s->local_polar_steps;
   // a5 + a6 (+ a8 when there is no local polar step): one sign-pack launch and one vote launch
   // over all blocks
-  std::vector<sm_sp_desc> sp(n);
+  std::vector<sm_sp_desc> sp;
+  sp.reserve(n);
   std::vector<sm_vote_desc> vd(n);
   for (int i = 0; i < n; ++i) {
     ns_class& cl = pl->classes[pl->class_of[i]];
@@ -658,18 +700,26 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
       if (rc != SM_OK) return rc;
     }
     const bool tap = s->signs_out && s->signs_out[i];
-    void* signs = tap ? s->signs_out[i] : at<void>(ctx, pl->off_signs[i]);
-    const long long stride = tap ? ((s->sign_fmt == SM_SIGN_INT8) ? d : 8 * ((d + 63) / 64)) : pl->sign_stride[i];
-    sm_sp_desc& S = sp[i];
-    S.u = u;
-    S.out = signs;
-    S.n = d;
-    S.batch_stride = cl.mat;
-    S.out_stride = stride;
-    S.bytes_per_row = 0;
-    S.cols = cl.cols;
-    S.ld = cl.cp;
-    S.blocks_per_row = S.block_begin = 0;
+    const bool in_gemm = fused && cl.fuse_signs;  // already in the internal buffer
+    void* signs = (tap && !in_gemm) ? s->signs_out[i] : at<void>(ctx, pl->off_signs[i]);
+    const long long stride =
+        (tap && !in_gemm) ? ((s->sign_fmt == SM_SIGN_INT8) ? d : 8 * ((d + 63) / 64)) : pl->sign_stride[i];
+    if (in_gemm) {
+      // d is a multiple of 64 here, so the tap's rows have the internal stride
+      if (tap) SM_HIP(ctx, hipMemcpyAsync(s->signs_out[i], signs, (size_t)stride * M, hipMemcpyDeviceToDevice, ctx->stream));
+    } else {
+      sm_sp_desc S;
+      S.u = u;
+      S.out = signs;
+      S.n = d;
+      S.batch_stride = cl.mat;
+      S.out_stride = stride;
+      S.bytes_per_row = 0;
+      S.cols = cl.cols;
+      S.ld = cl.cp;
+      S.blocks_per_row = S.block_begin = 0;
+      sp.push_back(S);
+    }
     float step = s->lr;
     if (s->update_rsqrt_mn) step = s->lr / sqrtf((float)cl.rows * (float)cl.cols);
     sm_vote_desc& V = vd[i];
@@ -695,8 +745,10 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
       V.w = nullptr;
     }
   }
-  rc = sm_launch_sign_pack_group(ctx, sp.data(), n, SM_BF16, s->sign_fmt, M);
-  if (rc != SM_OK) return rc;
+  if (!sp.empty()) {
+    rc = sm_launch_sign_pack_group(ctx, sp.data(), (int)sp.size(), SM_BF16, s->sign_fmt, M);
+    if (rc != SM_OK) return rc;
+  }
   rc = sm_launch_vote_group(ctx, vd.data(), n, s->sign_fmt);
   if (rc != SM_OK) return rc;
   if (Kp == 0 && s->d_out) {  // W was already stepped; the tap only re-derives the vote

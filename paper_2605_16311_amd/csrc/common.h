@@ -183,8 +183,17 @@ struct sm_gemm_prob {
   int tiles_m, tiles_n;  // filled by the launcher
   int tile_begin;        // filled by the launcher
   int layout;            // bit 0: A stored [K][M] (lda = its row length), bit 1: B stored [K][N]
+  // Optional sign output of a general (non-symmetric) bf16 product: the signs (x >= 0) of the
+  // leading sign_rows x sign_cols part of C[b], packed row-major into
+  // sign_out + b * sign_stride as in signmuon_sign_pack (sign_cols a multiple of 32).  C may
+  // then be null.
+  void* sign_out;
+  long long sign_stride;
+  int sign_rows, sign_cols;
+  int sign_fmt;
+  int pad_;
 };
-constexpr int SM_GEMM_MAX_PROB = 32;
+constexpr int SM_GEMM_MAX_PROB = 24;
 struct sm_gemm_args {
   int n_prob;
   int total_tiles;

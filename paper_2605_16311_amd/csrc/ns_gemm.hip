@@ -141,6 +141,12 @@ __device__ __forceinline__ void unpack2(unsigned w, bool f16, float& lo, float& 
   }
 }
 
+// x >= 0 for a bf16 bit pattern (IEEE comparison: -0 counts as >= 0, NaN does not)
+__device__ __forceinline__ unsigned ge0_bf16(unsigned h) {
+  const unsigned mag = h & 0x7FFFu;
+  return (mag == 0u) | (((h >> 15) == 0u) & (mag <= 0x7F80u));
+}
+
 // One TS x TS tile of one problem.  The four stage arrays are the kernel's own __shared__
 // variables, passed by reference so that every access keeps its identity after inlining.
 template <int TS, bool A_MN, bool B_MN, bool SYM, bool F16>
@@ -304,7 +310,7 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
   }
   const float alpha = args.alpha * s;
   const bool of16 = args.out_f16 != 0;
-  bf16_t* __restrict__ C = P.C + (long long)b * P.sC;
+  bf16_t* __restrict__ C = P.C ? P.C + (long long)b * P.sC : nullptr;
   // a fresh opaque thread id: the store addresses are worked out here, after the K loop,
   // instead of being carried through it in registers
   int etid = threadIdx.x;
@@ -363,7 +369,7 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
     }
   }
   __syncthreads();
-  {
+  if (SYM || C) {
     // rows: thread t handles chunk t % CPR of rows t / CPR + RPP * k
     const int rc = etid % CPR, rr = etid / CPR;
 #pragma unroll
@@ -374,7 +380,46 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
       const int gr = m0 + row, gc = n0 + rc * 8;
       if (gr < M && gc < N) {
         const long long off = (long long)gr * P.ldc + gc;
-        *reinterpret_cast<u32x4*>(C + off) = R ? add_r(v, R, off) : v;
+        const u32x4 w = R ? add_r(v, R, off) : v;
+        *reinterpret_cast<u32x4*>(C + off) = w;
+      }
+    }
+  }
+  if (!SYM && P.sign_out) {
+    // packed signs of the tile: NTH / TS threads per tile row, each turning CPT consecutive columns
+    // of the staged row into CPT / 8 bytes (1 bit) or CPT bytes (int8)
+    constexpr int TPR = NTH / TS, CPT = TS / TPR, NCH = CPT / 8;
+    const int row = etid / TPR, part = etid % TPR;
+    const int gr = m0 + row, gc0 = n0 + part * CPT;
+    const unsigned char* sp = stage(row >> 6) + (row & 63) * RB;
+    unsigned char* so = reinterpret_cast<unsigned char*>(P.sign_out) + (long long)b * P.sign_stride;
+    const long long e0 = (long long)gr * P.sign_cols + gc0;  // first entry; a multiple of 32
+    unsigned word = 0;
+#pragma unroll
+    for (int q = 0; q < NCH; ++q) {
+      const u32x4 w = *reinterpret_cast<const u32x4*>(sp + (((part * NCH + q) ^ (row & (CPR - 1))) << 4));
+      unsigned bits = 0;
+#pragma unroll
+      for (int h = 0; h < 4; ++h)
+        bits |= (ge0_bf16(w[h] & 0xFFFFu) << (2 * h)) | (ge0_bf16(w[h] >> 16) << (2 * h + 1));
+      const bool live = gr < P.sign_rows && gc0 + 8 * q < P.sign_cols;
+      if (P.sign_fmt == SM_SIGN_1BIT) {
+        word |= bits << (8 * (q & 3));
+        if ((q & 3) == 3) {
+          // 32 columns per store; sign_cols is a multiple of 32, so a word is live as a whole
+          if (live) *reinterpret_cast<unsigned*>(so + ((e0 + 8 * (q - 3)) >> 3)) = word;
+          word = 0;
+        }
+      } else if (live) {
+        u32x2 s8;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          unsigned v4 = 0;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) v4 |= (((bits >> (4 * h + k)) & 1u) ? 0x01u : 0xFFu) << (8 * k);
+          s8[h] = v4;
+        }
+        *reinterpret_cast<u32x2*>(so + e0 + 8 * q) = s8;
       }
     }
   }
@@ -520,6 +565,10 @@ int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, bool sym, int klass) {
     if (gram ? (P.layout != 0 && P.layout != 3) : (P.layout != 0 && P.layout != 2))
       return sm_fail(ctx, SM_EUNSUPPORTED, "internal: GEMM layout combination not built");
     if (!sm_aligned(P.R, 16)) return sm_fail(ctx, SM_EINVAL, "internal: GEMM R term misaligned");
+    if (!P.C && (sym || !P.sign_out)) return sm_fail(ctx, SM_EINVAL, "internal: GEMM without an output");
+    if (P.sign_out && (sym || args.out_f16 || P.R || P.sign_cols % 32 || P.sign_stride % 8 || !sm_aligned(P.sign_out, 8) ||
+                       (P.sign_fmt != SM_SIGN_1BIT && P.sign_fmt != SM_SIGN_INT8)))
+      return sm_fail(ctx, SM_EUNSUPPORTED, "internal: GEMM sign output needs a general bf16 product and cols % 32 == 0");
     if ((args.a_diag != 0.f || args.b_diag != 0.f) && !args.in_f16)
       return sm_fail(ctx, SM_EUNSUPPORTED, "internal: operand identity shift needs half-precision operands");
     if (args.in_f16 && (!sym || P.layout != 0))
@@ -558,7 +607,8 @@ int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, bool sym, int klass) {
       ctx->work_flop[klass] += 2.0 * mnk;
       const bool same = (P.A == P.B);
       ctx->work_bytes[klass] += 2.0 * P.batch * ((double)P.M * P.K + (same ? 0.0 : (double)P.N * P.K) +
-                                                 (double)P.M * P.N * (1 + (P.R != nullptr && P.R != P.A && P.R != P.B)));
+                                                 (double)P.M * P.N * ((P.C != nullptr) + (P.R != nullptr && P.R != P.A && P.R != P.B))) +
+                             (P.sign_out ? (double)P.batch * P.sign_stride : 0.0);
     }
   }
   {
