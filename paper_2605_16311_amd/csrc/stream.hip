@@ -596,6 +596,83 @@ int sm_launch_vote(signmuon_ctx* ctx, const sm_vote_args& v) {
   return SM_OK;
 }
 
+// Expanding vote over 1-bit signs, wide form: one thread = one 32-bit word of every worker's
+// buffer, counted bit-sliced (PLANES binary counter planes, M < 2^PLANES) and compared with
+// ceil(M/2) as in sm_vote_bits_kernel.  The 2048 votes of a wave are then spread over its
+// lanes so that every store (and every load of W) covers consecutive addresses: lane l
+// writes 8 consecutive bf16 per store (4 stores), and steps 4 consecutive weights per load
+// and store (8 of each).  For tables whose entries have n % 32 == 0, no counts output and, if
+// a voted matrix is asked for, the flat bf16 form.
+template <int PLANES>
+__global__ void __launch_bounds__(TPB) sm_vote_wide_kernel(const vote_g_args g) {
+  int di = 0;
+  while (di + 1 < g.n && (int)blockIdx.x >= g.d[di + 1].block_begin) ++di;
+  const vote_x_args& a = g.d[di];
+  const long long words = a.n >> 5;
+  const long long w0 = (long long)(blockIdx.x - a.block_begin) * TPB + (threadIdx.x & ~63);  // the wave's first word
+  const int lane = threadIdx.x & 63;
+  const long long wi = w0 + lane;
+  unsigned v = 0;
+  if (wi < words) {
+    const unsigned* base = reinterpret_cast<const unsigned*>(a.signs) + wi;
+    const long long stride_w = a.stride_bytes >> 2;
+    unsigned plane[PLANES];
+#pragma unroll
+    for (int k = 0; k < PLANES; ++k) plane[k] = 0;
+    for (int p = 0; p < a.M; ++p) {
+      unsigned carry = __builtin_nontemporal_load(base + (long long)p * stride_w);
+#pragma unroll
+      for (int k = 0; k < PLANES; ++k) {
+        const unsigned t = plane[k] & carry;
+        plane[k] ^= carry;
+        carry = t;
+      }
+    }
+    const unsigned T = (unsigned)((a.M + 1) / 2);
+    unsigned gt = 0, eq = ~0u;
+#pragma unroll
+    for (int k = PLANES - 1; k >= 0; --k) {
+      const unsigned tb = ((T >> k) & 1u) ? ~0u : 0u;
+      gt |= eq & plane[k] & ~tb;
+      eq &= ~(plane[k] ^ tb);
+    }
+    v = gt | eq;
+  }
+  if (a.voted) {
+    bf16_t* o = reinterpret_cast<bf16_t*>(a.voted) + w0 * 32;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      // chunk 64 k + lane of the wave's 256 chunks of 8 entries: byte (lane & 3) of word 16 k + lane / 4
+      const unsigned word = __shfl(v, 16 * k + (lane >> 2), 64);
+      const unsigned bits = (word >> (8 * (lane & 3))) & 0xFFu;
+      if (w0 + 16 * k + (lane >> 2) < words) {
+        u32x4 h;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          h[q] = (((bits >> (2 * q)) & 1u) ? 0x3F80u : 0xBF80u) | ((((bits >> (2 * q + 1)) & 1u) ? 0x3F80u : 0xBF80u) << 16);
+        *reinterpret_cast<u32x4*>(o + (64 * k + lane) * 8) = h;
+      }
+    }
+  }
+  if (a.w) {
+    float* wp = a.w + w0 * 32;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      // group 64 k + lane of the wave's 512 groups of 4 entries: nibble (lane & 7) of word 8 k + lane / 8
+      const unsigned word = __shfl(v, 8 * k + (lane >> 3), 64);
+      const unsigned bits = (word >> (4 * (lane & 7))) & 0xFu;
+      if (w0 + 8 * k + (lane >> 3) < words) {
+        float4 wv = *reinterpret_cast<float4*>(wp + (64 * k + lane) * 4);
+        wv.x = __fsub_rn(wv.x, __fmul_rn(a.lr, (bits & 1u) ? 1.0f : -1.0f));
+        wv.y = __fsub_rn(wv.y, __fmul_rn(a.lr, (bits & 2u) ? 1.0f : -1.0f));
+        wv.z = __fsub_rn(wv.z, __fmul_rn(a.lr, (bits & 4u) ? 1.0f : -1.0f));
+        wv.w = __fsub_rn(wv.w, __fmul_rn(a.lr, (bits & 8u) ? 1.0f : -1.0f));
+        *reinterpret_cast<float4*>(wp + (64 * k + lane) * 4) = wv;
+      }
+    }
+  }
+}
+
 int sm_launch_vote_group(signmuon_ctx* ctx, const sm_vote_desc* descs, int n, int fmt) {
   int done = 0;
   while (done < n) {
@@ -603,19 +680,37 @@ int sm_launch_vote_group(signmuon_ctx* ctx, const sm_vote_desc* descs, int n, in
     vote_g_args a;
     a.n = g;
     a.pad_ = 0;
+    // the wide kernel serves tables made only of whole 32-entry words, bf16 flat outputs, no counts
+    bool wide = (fmt == SM_SIGN_1BIT);
+    int max_m = 0;
+    for (int i = 0; i < g && wide; ++i) {
+      const sm_vote_desc& d = descs[done + i];
+      wide = d.n % 32 == 0 && !d.counts && d.M < 256 && d.stride_bytes % 4 == 0 && sm_aligned(d.signs, 4) &&
+             (!d.voted || (d.vfmt == SM_VOTE_BF16 && d.ld == d.cols && sm_aligned(d.voted, 16))) &&
+             (!d.w || sm_aligned(d.w, 16));
+      max_m = std::max(max_m, d.M);
+    }
     long long blocks = 0;
     for (int i = 0; i < g; ++i) {
       a.d[i] = descs[done + i];
       a.d[i].block_begin = (int)blocks;
-      blocks += (((a.d[i].n + 3) / 4) + TPB - 1) / TPB;
+      const long long threads = wide ? a.d[i].n / 32 : (a.d[i].n + 3) / 4;
+      blocks += (threads + TPB - 1) / TPB;
     }
     if (blocks > 0x7FFFFFFFLL) return sm_fail(ctx, SM_EUNSUPPORTED, "vote: too many entries for one launch");
     if (blocks > 0) {
       sm_launch_scope sc(ctx, SM_K_VOTE);
-      if (fmt == SM_SIGN_1BIT)
-        hipLaunchKernelGGL(sm_vote_expand_kernel<SM_SIGN_1BIT>, dim3((unsigned)blocks), dim3(TPB), 0, ctx->stream, a);
+      const dim3 grid((unsigned)blocks), block(TPB);
+      if (wide && max_m < 8)
+        hipLaunchKernelGGL(sm_vote_wide_kernel<3>, grid, block, 0, ctx->stream, a);
+      else if (wide && max_m < 32)
+        hipLaunchKernelGGL(sm_vote_wide_kernel<5>, grid, block, 0, ctx->stream, a);
+      else if (wide)
+        hipLaunchKernelGGL(sm_vote_wide_kernel<8>, grid, block, 0, ctx->stream, a);
+      else if (fmt == SM_SIGN_1BIT)
+        hipLaunchKernelGGL(sm_vote_expand_kernel<SM_SIGN_1BIT>, grid, block, 0, ctx->stream, a);
       else
-        hipLaunchKernelGGL(sm_vote_expand_kernel<SM_SIGN_INT8>, dim3((unsigned)blocks), dim3(TPB), 0, ctx->stream, a);
+        hipLaunchKernelGGL(sm_vote_expand_kernel<SM_SIGN_INT8>, grid, block, 0, ctx->stream, a);
     }
     SM_HIP(ctx, hipGetLastError());
     done += g;

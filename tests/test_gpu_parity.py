@@ -161,6 +161,31 @@ def test_vote_bit_exact(P, ctx, M, n):
         assert np.array_equal(vf.cpu().numpy()[:n], vote_ref.astype(np.float32)) and np.all(vf.cpu().numpy()[n:] == 0)
 
 
+@pytest.mark.parametrize("M", [1, 2, 3, 7, 8, 31, 32, 100, 255, 256])
+@pytest.mark.parametrize("n", [32, 64 * 37, 32 * 2049, 256 * 300 + 32])
+def test_vote_word_aligned_without_counts(P, ctx, M, n):
+    """n % 32 == 0, no counts: the form the step uses (bit-sliced counting, one thread per 32-bit word);
+    voted bf16 and the fused update in one call, against the scalar definition (eq. mv_def)."""
+    rng = wl.rng_for(27, block=M, worker=n)
+    S = rng.choice(np.array([-1, 1], np.int8), size=(M, n), p=[0.5, 0.5])
+    if M % 2 == 0:
+        S[: M // 2, 3::17] = 1
+        S[M // 2:, 3::17] = -1                                # forced ties -> +1
+    packed = np.stack([O.pack_bits((S[p] > 0).astype(np.uint8)) for p in range(M)])
+    stride = packed.shape[1]
+    vote_ref, _ = O.majority_vote_int8(S)
+    w0 = wl.normal((n,), stream=28, block=n)
+    lr = 0.0625
+    w_ref = O.apply_update(w0.reshape(1, n), vote_ref.reshape(1, n), lr, dtype=np.float32).reshape(n)
+    w = dev(np.concatenate([w0, np.full(8, 3.0, np.float32)]))
+    vb16 = torch.full((n + 8,), 5.0, dtype=torch.bfloat16, device="cuda")
+    P.signmuon_majority_vote(ctx, dev(packed), "1bit", M, n, stride, voted=vb16, vfmt="bf16", w=w, lr_scaled=lr)
+    gv = bf16_host(vb16)
+    assert np.array_equal(gv[:n], vote_ref.astype(np.float32)) and np.all(gv[n:] == 5.0), (M, n)
+    gw = w.cpu().numpy()
+    assert np.array_equal(gw[:n].view(np.uint32), w_ref.view(np.uint32)) and np.all(gw[n:] == 3.0), (M, n)
+
+
 def test_vote_ignores_garbage_tail_bits_and_dropped_worker(P, ctx):
     M, n = 5, 70
     rng = wl.rng_for(25)
