@@ -332,6 +332,29 @@ def test_step_mixed_set(P, ctx, sign_fmt, Kp):
     run_step_case(P, ctx, shapes, 3, sign_fmt=sign_fmt, Kp=Kp, wd=0.1, rsqrt=(Kp > 0))
 
 
+def test_step_signs_written_by_the_apply_alone(P, ctx):
+    """Without a u_out tap the last apply writes only the packed signs (U is never stored).  The same step
+    with all taps (checked against the oracle by the cases above) must give the same signs, counts and W."""
+    shapes, M = [(128, 256), (256, 128), (192, 192), (64, 100)], 3      # the last one cannot be packed by the GEMM
+    outs = []
+    for tapped in (True, False):
+        w = [dev(wl.weights(r, c, block=i)) for i, (r, c) in enumerate(shapes)]
+        mom = [torch.zeros((M, r, c), device="cuda") for r, c in shapes]
+        grad = [dev(wl.normal((M, r, c), stream=29, block=i)) for i, (r, c) in enumerate(shapes)]
+        d = [r * c for r, c in shapes]
+        signs = [torch.zeros((M, O.packed_stride_bytes(x)), dtype=torch.uint8, device="cuda") for x in d]
+        counts = [torch.zeros((x,), dtype=torch.int32, device="cuda") for x in d]
+        u_out = [torch.zeros((M, r, c), dtype=torch.bfloat16, device="cuda") for r, c in shapes] if tapped else None
+        plan = P.StepPlan(w, mom, grad, beta=0.9, lr=1e-2, ns_steps=5, sign_fmt="1bit", local_polar_steps=2,
+                          signs_out=signs, counts_out=counts, u_out=u_out)
+        P.signmuon_step(ctx, plan)
+        torch.cuda.synchronize()
+        outs.append(([t.cpu().numpy() for t in signs], [t.cpu().numpy() for t in counts], [t.cpu().numpy() for t in w]))
+    for a, b in zip(outs[0], outs[1]):
+        for x, y in zip(a, b):
+            assert np.array_equal(x.view(np.uint8), y.view(np.uint8))
+
+
 def test_step_spectral(P, ctx):
     run_step_case(P, ctx, [(128, 256), (256, 128)], 2, sign_fmt="1bit", Kp=2, scale="spectral")
 
