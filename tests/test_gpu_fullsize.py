@@ -101,6 +101,112 @@ def test_resnet50_step_in_bench_configuration(P):
     full_step_check(P, "resnet50", ns_blocks={0, 1, 2, 3, 4, 5})
 
 
+def progress(msg):
+    """Progress line for the multi-minute tests: printed, and appended to a log next to the other GPU-run
+    output so that a watcher of that folder sees the test advancing while pytest captures stdout."""
+    print(msg, flush=True)
+    try:
+        import os
+        out = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+        os.makedirs(out, exist_ok=True)
+        with open(os.path.join(out, "fullsize_progress.log"), "a") as f:
+            f.write(msg + "\n")
+    except OSError:
+        pass
+
+
+def streamed_full_step_check(P, name, ns_items, mom_workers):
+    """One step of a large workload from zero momentum, in the benchmark's configuration, checked block by
+    block so that the host only ever holds one block.  Bit-exact on ALL blocks and workers: signs, counts
+    (hence the vote) and W; momentum bit-exact on all blocks for the workers in mom_workers; Newton-Schulz
+    outputs against the float32 oracle on the (block, worker) pairs in ns_items (one per distinct shape) and
+    by the rank bound on the rest."""
+    import bench
+    cfg, w, mom, grad = bench.make_inputs(name, torch, torch.device("cuda:0"))
+    shapes, M = cfg["shapes"], cfg["M"]
+    K, Kp, fmt = cfg["ns_steps"], cfg["local_polar_steps"], cfg["sign_fmt"]
+    lr, beta = 1e-3, 0.9
+    d = [r * c for r, c in shapes]
+    stride = [O.packed_stride_bytes(x) if fmt == "1bit" else x for x in d]
+    w0 = [t.clone() for t in w]
+    signs = [torch.zeros((M, s), dtype=torch.uint8, device="cuda") for s in stride]
+    counts = [torch.zeros((x,), dtype=torch.int32, device="cuda") for x in d]
+    u_out = [torch.zeros((M, r, c), dtype=torch.bfloat16, device="cuda") for r, c in shapes]
+    d_out = [torch.zeros((r, c), dtype=torch.bfloat16, device="cuda") for r, c in shapes]
+    ctx = P.Context()
+    plan = P.StepPlan(w, mom, grad, beta=beta, lr=lr, ns_steps=K, sign_fmt=fmt, local_polar_steps=Kp,
+                      signs_out=signs, counts_out=counts, u_out=u_out, d_out=d_out)
+    P.signmuon_step(ctx, plan)
+    torch.cuda.synchronize()
+    ns_blocks = {i for i, _ in ns_items}
+    ties = 0
+    for i, (r, c) in enumerate(shapes):
+        progress(f"{name}: checking block {i} of {len(shapes)} ({r} x {c})")
+        workers = sorted(set(mom_workers) | {p for bi, p in ns_items if bi == i})
+        G = grad[i][workers].cpu().numpy()
+        m_ref = O.momentum_update(np.zeros_like(G), G, None, beta, 0.0, dtype=np.float32)
+        del G
+        assert np.array_equal(mom[i][workers].cpu().numpy().view(np.uint32), m_ref.view(np.uint32)), f"momentum block {i}"
+        U = u_out[i].float().cpu().numpy()
+        assert np.isfinite(U).all()
+        for p in range(M):
+            x = U[p].reshape(-1)
+            assert float(np.dot(x, x)) <= min(r, c) * 1.02, f"block {i} worker {p}: ||U||_F^2 > rank bound"
+        for (bi, p) in ns_items:
+            if bi == i:
+                ref = O.polar_ns(m_ref[workers.index(p)], K, dtype=np.float32)
+                rel, agree = rel_and_agree(U[p], ref)
+                assert rel <= 2e-2 and agree >= 0.999, f"U block {i} worker {p}: rel {rel:.3e} agree {agree:.5f}"
+        del m_ref
+        bits_ref = np.stack([O.pack_bits(O.sign_entries(U[p])) for p in range(M)])
+        vote_ref, c_ref = O.majority_vote_bits(bits_ref, M, d[i])
+        g_signs = signs[i].cpu().numpy()
+        if fmt == "1bit":
+            assert np.array_equal(g_signs, bits_ref), f"signs block {i}"
+        else:
+            # +-1 bytes: every byte is +1 or -1 and the +1 pattern is the oracle's bit pattern; the int32 sum
+            # is 2 c - M (checked against the int8 oracle itself on the first block)
+            s8 = g_signs.view(np.int8)
+            assert np.all(np.abs(s8) == 1), f"signs block {i}: byte other than +-1"
+            assert np.array_equal(np.stack([O.pack_bits((s8[p] > 0).astype(np.uint8)) for p in range(M)]), bits_ref)
+            if i == 0:
+                s_ref = np.stack([O.signs_pm1(U[p]).reshape(-1) for p in range(M)])
+                assert np.array_equal(s8, s_ref)
+                v8, t8 = O.majority_vote_int8(s_ref)
+                assert np.array_equal(v8, vote_ref) and np.array_equal(t8, 2 * c_ref - M)
+                del s_ref
+            c_ref = 2 * c_ref - M
+            ties += int(np.sum(c_ref == 0))
+        del U, bits_ref, g_signs
+        assert np.array_equal(counts[i].cpu().numpy(), c_ref), f"counts block {i}"
+        D = d_out[i].float().cpu().numpy()
+        S_bar = vote_ref.reshape(r, c)
+        if Kp == 0:
+            assert np.array_equal(D, S_bar.astype(np.float32))
+        else:
+            x = D.reshape(-1)
+            assert float(np.dot(x, x)) <= min(r, c) * 1.02
+            if i in ns_blocks:
+                ref = O.local_polar(S_bar, Kp, dtype=np.float32)
+                rel, agree = rel_and_agree(D, ref)
+                assert rel <= 2e-2 and agree >= 0.999, f"D block {i}: rel {rel:.3e} agree {agree:.5f}"
+        w_ref = O.apply_update(w0[i].cpu().numpy(), D, lr, False, dtype=np.float32)
+        assert np.array_equal(w[i].cpu().numpy().view(np.uint32), w_ref.view(np.uint32)), f"W block {i}"
+    ctx.close()
+    return ties, sum(d)
+
+
+def test_large_step_in_bench_configuration(P):
+    """8 x 4096 x 4096 and 8 x 4096 x 11008, M = 16, Student-t(3) gradients, 1-bit vote, local polar step."""
+    streamed_full_step_check(P, "large", ns_items=[(0, 0), (8, 15)], mom_workers=(0, 15))
+
+
+def test_int8vote_step_in_bench_configuration(P):
+    """32 x 2048 x 8192, M = 16, int8 signs summed in int32 (iid workers: about a fifth of the entries tie)."""
+    ties, total = streamed_full_step_check(P, "int8vote", ns_items=[(0, 3)], mom_workers=(0, 15))
+    assert ties > 0.1 * total
+
+
 def test_int8_vote_path_m16_with_ties(P):
     """The int8 transport at M = 16 (iid workers: about a fifth of the entries tie), with a local polar step."""
     shapes, M = [(256, 1024), (1024, 256), (192, 320)], 16
