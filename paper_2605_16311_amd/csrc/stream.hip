@@ -673,6 +673,68 @@ __global__ void __launch_bounds__(TPB) sm_vote_wide_kernel(const vote_g_args g) 
   }
 }
 
+// Expanding vote over int8 signs, wide form: one thread = 16 consecutive entries (one 16-byte load per
+// worker), int32 sums, then any of: counts, voted int8 / bf16 (flat), fused W update.  For tables whose
+// entries have n % 16 == 0 and 16-byte aligned rows.
+__global__ void __launch_bounds__(TPB) sm_vote_int8_wide_kernel(const vote_g_args g) {
+  int di = 0;
+  while (di + 1 < g.n && (int)blockIdx.x >= g.d[di + 1].block_begin) ++di;
+  const vote_x_args& a = g.d[di];
+  const long long t = (long long)(blockIdx.x - a.block_begin) * TPB + threadIdx.x;
+  const long long e0 = t * 16;
+  if (e0 >= a.n) return;
+  int c[16];
+#pragma unroll
+  for (int k = 0; k < 16; ++k) c[k] = 0;
+  const unsigned char* base = reinterpret_cast<const unsigned char*>(a.signs) + e0;
+  for (int p = 0; p < a.M; ++p) {
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + (long long)p * a.stride_bytes));
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int k = 0; k < 4; ++k) c[4 * q + k] += (int)(signed char)(v[q] >> (8 * k));
+  }
+  if (a.counts) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      *reinterpret_cast<int4*>(a.counts + e0 + 4 * q) = make_int4(c[4 * q], c[4 * q + 1], c[4 * q + 2], c[4 * q + 3]);
+  }
+  if (a.w) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float4 wv = *reinterpret_cast<float4*>(a.w + e0 + 4 * q);
+      wv.x = __fsub_rn(wv.x, __fmul_rn(a.lr, c[4 * q] >= 0 ? 1.0f : -1.0f));
+      wv.y = __fsub_rn(wv.y, __fmul_rn(a.lr, c[4 * q + 1] >= 0 ? 1.0f : -1.0f));
+      wv.z = __fsub_rn(wv.z, __fmul_rn(a.lr, c[4 * q + 2] >= 0 ? 1.0f : -1.0f));
+      wv.w = __fsub_rn(wv.w, __fmul_rn(a.lr, c[4 * q + 3] >= 0 ? 1.0f : -1.0f));
+      *reinterpret_cast<float4*>(a.w + e0 + 4 * q) = wv;
+    }
+  }
+  if (a.voted) {
+    if (a.vfmt == SM_VOTE_INT8) {
+      u32x4 o;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        unsigned v4 = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v4 |= (c[4 * q + k] >= 0 ? 0x01u : 0xFFu) << (8 * k);
+        o[q] = v4;
+      }
+      *reinterpret_cast<u32x4*>(reinterpret_cast<unsigned char*>(a.voted) + e0) = o;
+    } else {  // bf16, flat
+      bf16_t* ob = reinterpret_cast<bf16_t*>(a.voted) + e0;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        u32x4 o;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          o[q] = (c[8 * h + 2 * q] >= 0 ? 0x3F80u : 0xBF80u) | ((c[8 * h + 2 * q + 1] >= 0 ? 0x3F80u : 0xBF80u) << 16);
+        *reinterpret_cast<u32x4*>(ob + 8 * h) = o;
+      }
+    }
+  }
+}
+
 int sm_launch_vote_group(signmuon_ctx* ctx, const sm_vote_desc* descs, int n, int fmt) {
   int done = 0;
   while (done < n) {
@@ -690,11 +752,20 @@ int sm_launch_vote_group(signmuon_ctx* ctx, const sm_vote_desc* descs, int n, in
              (!d.w || sm_aligned(d.w, 16));
       max_m = std::max(max_m, d.M);
     }
+    // the wide int8 kernel: whole 16-entry groups, 16-byte aligned rows and outputs, int8 or flat bf16 votes
+    bool wide8 = (fmt == SM_SIGN_INT8);
+    for (int i = 0; i < g && wide8; ++i) {
+      const sm_vote_desc& d = descs[done + i];
+      wide8 = d.n % 16 == 0 && d.stride_bytes % 16 == 0 && sm_aligned(d.signs, 16) &&
+              (!d.voted || (d.vfmt == SM_VOTE_INT8 && sm_aligned(d.voted, 16)) ||
+               (d.vfmt == SM_VOTE_BF16 && d.ld == d.cols && sm_aligned(d.voted, 16))) &&
+              (!d.w || sm_aligned(d.w, 16)) && (!d.counts || sm_aligned(d.counts, 16));
+    }
     long long blocks = 0;
     for (int i = 0; i < g; ++i) {
       a.d[i] = descs[done + i];
       a.d[i].block_begin = (int)blocks;
-      const long long threads = wide ? a.d[i].n / 32 : (a.d[i].n + 3) / 4;
+      const long long threads = wide ? a.d[i].n / 32 : wide8 ? a.d[i].n / 16 : (a.d[i].n + 3) / 4;
       blocks += (threads + TPB - 1) / TPB;
     }
     if (blocks > 0x7FFFFFFFLL) return sm_fail(ctx, SM_EUNSUPPORTED, "vote: too many entries for one launch");
@@ -707,6 +778,8 @@ int sm_launch_vote_group(signmuon_ctx* ctx, const sm_vote_desc* descs, int n, in
         hipLaunchKernelGGL(sm_vote_wide_kernel<5>, grid, block, 0, ctx->stream, a);
       else if (wide)
         hipLaunchKernelGGL(sm_vote_wide_kernel<8>, grid, block, 0, ctx->stream, a);
+      else if (wide8)
+        hipLaunchKernelGGL(sm_vote_int8_wide_kernel, grid, block, 0, ctx->stream, a);
       else if (fmt == SM_SIGN_1BIT)
         hipLaunchKernelGGL(sm_vote_expand_kernel<SM_SIGN_1BIT>, grid, block, 0, ctx->stream, a);
       else

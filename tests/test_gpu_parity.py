@@ -186,6 +186,36 @@ def test_vote_word_aligned_without_counts(P, ctx, M, n):
     assert np.array_equal(gw[:n].view(np.uint32), w_ref.view(np.uint32)) and np.all(gw[n:] == 3.0), (M, n)
 
 
+@pytest.mark.parametrize("M", [1, 2, 16, 127, 300])
+@pytest.mark.parametrize("n", [16, 4096, 65536 + 16])
+def test_vote_int8_sixteen_entry_groups(P, ctx, M, n):
+    """int8 signs with n % 16 == 0 and aligned rows (one thread per 16 entries): int32 sums, voted int8 and
+    bf16, fused update, against the scalar definition; sums beyond the int8 range at M = 300."""
+    rng = wl.rng_for(30, block=M, worker=n)
+    S = rng.choice(np.array([-1, 1], np.int8), size=(M, n), p=[0.5, 0.5])
+    if M % 2 == 0:
+        S[: M // 2, 1::13] = 1
+        S[M // 2:, 1::13] = -1                                # forced ties -> +1
+    S[:, 0] = 1                                               # sum = M (overflows int8 at M = 300)
+    vote_ref, tot_ref = O.majority_vote_int8(S)
+    w0 = wl.normal((n,), stream=31, block=n)
+    lr = 0.03125
+    w_ref = O.apply_update(w0.reshape(1, n), vote_ref.reshape(1, n), lr, dtype=np.float32).reshape(n)
+    d_signs = dev(S)
+    cnt = torch.full((n + 16,), -7, dtype=torch.int32, device="cuda")
+    w = dev(np.concatenate([w0, np.full(16, 3.0, np.float32)]))
+    v8 = torch.full((n + 16,), 9, dtype=torch.int8, device="cuda")
+    P.signmuon_majority_vote(ctx, d_signs, "int8", M, n, n, voted=v8, vfmt="int8", counts=cnt, w=w, lr_scaled=lr)
+    assert np.array_equal(v8.cpu().numpy()[:n], vote_ref) and np.all(v8.cpu().numpy()[n:] == 9)
+    assert np.array_equal(cnt.cpu().numpy()[:n], tot_ref) and np.all(cnt.cpu().numpy()[n:] == -7)
+    gw = w.cpu().numpy()
+    assert np.array_equal(gw[:n].view(np.uint32), w_ref.view(np.uint32)) and np.all(gw[n:] == 3.0)
+    vb16 = torch.full((n + 16,), 5.0, dtype=torch.bfloat16, device="cuda")
+    P.signmuon_majority_vote(ctx, d_signs, "int8", M, n, n, voted=vb16, vfmt="bf16")
+    gv = bf16_host(vb16)
+    assert np.array_equal(gv[:n], vote_ref.astype(np.float32)) and np.all(gv[n:] == 5.0)
+
+
 def test_vote_ignores_garbage_tail_bits_and_dropped_worker(P, ctx):
     M, n = 5, 70
     rng = wl.rng_for(25)
