@@ -67,14 +67,19 @@ def make_inputs(name, torch, device):
     return cfg, w, mom, grad
 
 
-def run_workload(name, steps, warmup, torch, P, B):
+def run_workload(name, steps, warmup, torch, P, B, scale="fro"):
     device = torch.device("cuda:0")
     cfg, w, mom, grad = make_inputs(name, torch, device)
     shapes, M = cfg["shapes"], cfg["M"]
     K, Kp = cfg["ns_steps"], cfg["local_polar_steps"]
     ctx = P.Context()
+    v0 = None
+    if scale == "spectral":
+        gen = torch.Generator(device=device)
+        gen.manual_seed(7)
+        v0 = [torch.randn((M, c), generator=gen, device=device) for _, c in shapes]
     plan = P.StepPlan(w, mom, grad, beta=0.9, lr=1e-3, ns_steps=K, sign_fmt=cfg["sign_fmt"],
-                      local_polar_steps=Kp, scale="fro")
+                      local_polar_steps=Kp, scale=scale, power_iters=2, v0=v0)
     for _ in range(warmup):
         P.signmuon_step(ctx, plan)
     torch.cuda.synchronize()
@@ -243,6 +248,8 @@ def main():
     ap.add_argument("--workload", default="nanogpt124m")
     ap.add_argument("--also", default="resnet50", help="second workload reported in the same line ('' to skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--scale", default="fro", choices=["fro", "spectral"],
+                    help="scale of Alg. PolarNS: Frobenius norm (default) or PowerIter with P = 2")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run three 1 GiB device copies (torch): a kernel of known traffic for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -266,7 +273,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
-    main_res = run_workload(args.workload, args.steps, args.warmup, torch, P, B)
+    main_res = run_workload(args.workload, args.steps, args.warmup, torch, P, B, scale=args.scale)
     also = None
     if args.also and args.also != args.workload:
         also = run_workload(args.also, max(args.steps * 5, 50), args.warmup, torch, P, B)
@@ -290,7 +297,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "M": main_res["M"], "blocks": main_res["n_blocks"],
-                   "entries": main_res["entries"], "ns_steps": 5, "scale": "fro"},
+                   "entries": main_res["entries"], "ns_steps": 5, "scale": args.scale},
         "roofline": {"kernel": dom_name, "bound": dom["bound"], "achieved": ach, "peak": peak, "unit": unit,
                      "frac": ach / peak, "traffic": traffic, "avg_launch_ms": dom["avg_launch_ms"],
                      "flop_per_launch": dom["flop_per_launch"], "bytes_per_launch": dom["bytes_per_launch"]},

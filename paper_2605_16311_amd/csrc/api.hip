@@ -103,7 +103,7 @@ int get_plan(signmuon_ctx* ctx, int n, const int* rows, const int* cols, int M, 
     off += (bytes + 255) / 256 * 256;
     return o;
   };
-  long long max_pi = 0;
+  long long total_pi = 0;
   for (auto& c : pl->classes) {
     const long long batch = (long long)c.count * M;
     c.off_x[0] = take((size_t)batch * c.mat * 2);
@@ -118,9 +118,9 @@ int get_plan(signmuon_ctx* ctx, int n, const int* rows, const int* cols, int M, 
     c.off_sig = take((size_t)batch * 4);
     c.off_inv = take((size_t)batch * 4);
     c.off_partial = take((size_t)batch * c.chunks * 4);
-    max_pi = std::max(max_pi, (long long)M * (c.rows + c.cols));
+    total_pi += (long long)c.count * M * (sm_round_up(c.rows, 8) + c.cp * (1 + (c.rows + SM_PI_ROW_CHUNK - 1) / SM_PI_ROW_CHUNK));
   }
-  pl->off_pi = take((size_t)max_pi * 4);
+  pl->off_pi = take((size_t)total_pi * 4);
   pl->off_signs.resize(n);
   pl->sign_stride.resize(n);
   for (auto& c : pl->classes) {
@@ -448,6 +448,40 @@ int run_ns(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coe
   return run_ns_stepwise(ctx, pl, mult, steps, coeffs, use_scale, cur_io, signs);
 }
 
+// Spectral scale of Alg. PolarNS for every block of the plan: `items` matrices per block starting at
+// matrix (index in class) * items_stride of buffer `buf` of its class; v0[i] is block i's start vectors.
+int spectral_sigma(signmuon_ctx* ctx, ns_plan* pl, int buf, int items, int items_stride, const float* const* v0,
+                   int P, float eps) {
+  const int n = (int)pl->rows.size();
+  std::vector<sm_pi_desc> d(n);
+  float* scratch = at<float>(ctx, pl->off_pi);
+  for (int i = 0; i < n; ++i) {
+    ns_class& cl = pl->classes[pl->class_of[i]];
+    const long long first = (long long)pl->index_in_class[i] * items_stride;
+    const int up = (int)sm_round_up(cl.rows, 8);
+    sm_pi_desc& D = d[i];
+    D.x = at<bf16_t>(ctx, cl.off_x[buf]) + first * cl.mat;
+    D.stride = cl.mat;
+    D.v0 = v0[i];
+    D.v0_stride = cl.cols;
+    D.u = scratch;
+    const int chunks = (cl.rows + SM_PI_ROW_CHUNK - 1) / SM_PI_ROW_CHUNK;
+    D.v = scratch + (long long)items * up;
+    D.part = D.v + (long long)items * cl.cp;
+    D.chunks = chunks;
+    D.pad_ = 0;
+    scratch += (long long)items * (up + (long long)cl.cp * (1 + chunks));
+    D.sigma = at<float>(ctx, cl.off_sig) + first;
+    D.rows = cl.rows;
+    D.cols = cl.cols;
+    D.ld = cl.cp;
+    D.up = up;
+    D.items = items;
+    D.block_begin = 0;
+  }
+  return sm_launch_power_iter_group(ctx, d.data(), n, P, eps);
+}
+
 bool bad_coeffs(const float* c) { return !c || !isfinite(c[0]) || !isfinite(c[1]) || !isfinite(c[2]); }
 
 }  // namespace
@@ -517,8 +551,7 @@ int signmuon_polar_ns(signmuon_ctx* ctx, void* x, int dtype, int batch, int rows
     if (rc != SM_OK) return rc;
     use_scale = true;
   } else if (scale == SM_SCALE_SPECTRAL) {
-    rc = sm_launch_power_iter(ctx, at<bf16_t>(ctx, cl.off_x[0]), rows, cols, cl.cp, cl.mat, batch, power_iters, eps, v0,
-                              cols, at<float>(ctx, pl->off_pi), at<float>(ctx, cl.off_sig));
+    rc = spectral_sigma(ctx, pl, 0, batch, batch, &v0, power_iters, eps);
     if (rc != SM_OK) return rc;
     rc = sm_launch_inv_sigma(ctx, at<float>(ctx, cl.off_sig), batch, eps, false, at<float>(ctx, cl.off_inv));
     if (rc != SM_OK) return rc;
@@ -654,14 +687,8 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
       }
       use_scale = true;
     } else if (spectral) {
-      for (int i = 0; i < n; ++i) {
-        ns_class& cl = pl->classes[pl->class_of[i]];
-        const long long first = (long long)pl->index_in_class[i] * M;
-        rc = sm_launch_power_iter(ctx, at<bf16_t>(ctx, cl.off_x[0]) + first * cl.mat, cl.rows, cl.cols, cl.cp, cl.mat,
-                                  M, s->power_iters, s->eps, s->v0[i], cl.cols, at<float>(ctx, pl->off_pi),
-                                  at<float>(ctx, cl.off_sig) + first);
-        if (rc != SM_OK) return rc;
-      }
+      rc = spectral_sigma(ctx, pl, 0, M, M, s->v0, s->power_iters, s->eps);
+      if (rc != SM_OK) return rc;
       for (auto& cl : pl->classes) {
         rc = sm_launch_inv_sigma(ctx, at<float>(ctx, cl.off_sig), cl.count * M, s->eps, false, at<float>(ctx, cl.off_inv));
         if (rc != SM_OK) return rc;
@@ -777,14 +804,9 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
     }
     use_scale2 = true;
   } else if (spectral) {
-    for (int i = 0; i < n; ++i) {
-      ns_class& cl = pl->classes[pl->class_of[i]];
-      const int idx = pl->index_in_class[i];
-      rc = sm_launch_power_iter(ctx, at<bf16_t>(ctx, cl.off_x[cur ^ 1]) + (long long)idx * cl.mat, cl.rows, cl.cols, cl.cp,
-                                cl.mat, 1, s->power_iters, s->eps, s->v0[i], cl.cols, at<float>(ctx, pl->off_pi),
-                                at<float>(ctx, cl.off_sig) + idx);
-      if (rc != SM_OK) return rc;
-    }
+    // worker 0's start vector serves the voted matrix of each block
+    rc = spectral_sigma(ctx, pl, cur ^ 1, 1, 1, s->v0, s->power_iters, s->eps);
+    if (rc != SM_OK) return rc;
     for (auto& cl : pl->classes) {
       rc = sm_launch_inv_sigma(ctx, at<float>(ctx, cl.off_sig), cl.count, s->eps, false, at<float>(ctx, cl.off_inv));
       if (rc != SM_OK) return rc;

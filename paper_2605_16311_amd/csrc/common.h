@@ -212,7 +212,23 @@ struct sm_gemm_args {
 int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, bool sym, int klass);
 
 // ---------------------------------------------------------------- power iteration (poweriter.hip)
-// sigma[b] = PowerIter(X[b], P, eps, v0[b]); X bf16 [rows][ld]; scratch: (rows + 2*cols + 4) floats per batch
-int sm_launch_power_iter(signmuon_ctx* ctx, const bf16_t* x, int rows, int cols, int ld, long long stride,
-                         int batch, int P, float eps, const float* v0, long long v0_stride, float* scratch,
-                         float* sigma);
+// sigma[item] = PowerIter(X[item], P, eps, v0[item]) for the `items` matrices of each table entry.
+struct sm_pi_desc {
+  const bf16_t* x;      // [items][rows][ld], zero beyond cols in every row
+  long long stride;     // elements between matrices
+  const float* v0;      // [items] start vectors of cols floats, v0_stride floats apart
+  long long v0_stride;
+  float* u;             // scratch [items][up]
+  float* v;             // scratch [items][ld]
+  float* part;          // scratch [items][chunks][ld]
+  float* sigma;         // [items]
+  int rows, cols, ld;   // ld a multiple of 64
+  int up;               // rows rounded up to a multiple of 8
+  int items;
+  int chunks;           // ceil(rows / SM_PI_ROW_CHUNK)
+  int block_begin;      // filled by the launcher
+  int pad_;
+};
+constexpr int SM_PI_MAX_GROUP = 40;
+constexpr int SM_PI_ROW_CHUNK = 128;
+int sm_launch_power_iter_group(signmuon_ctx* ctx, const sm_pi_desc* descs, int n, int P, float eps);

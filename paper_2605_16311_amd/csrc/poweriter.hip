@@ -1,13 +1,24 @@
 // Alg. PowerIter (spectral-norm estimate for the spectral scale of PolarNS):
 //   v <- v0 / (|v0| + eps);  P times { u = X v, u /= |u| + eps;  v = X^T u, v /= |v| + eps };
 //   sigma = |X v|.
-// X is the bf16 working copy [rows][ld]; vectors and sums are fp32.  Every
-// reduction runs in a fixed order (no atomics), so sigma is reproducible.
+// Grouped over a table of weight blocks, M matrices each: every pass over the X of ALL blocks and
+// workers is one launch (two per table when the set has more blocks than a table holds).
+// X is the bf16 working copy [rows][ld] with zero padding up to ld (a multiple of 64); vectors
+// and sums are fp32, u padded to a multiple of 8 and v to ld with zeros.  Every reduction runs
+// in a fixed order (no atomics), so sigma is reproducible.
 #include "common.h"
 
 namespace {
 
 constexpr int TPB = 256;
+
+struct pi_args {
+  int n;
+  int P_unused;
+  float eps;
+  int pad_;
+  sm_pi_desc d[SM_PI_MAX_GROUP];
+};
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -15,90 +26,184 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-// u[b][i] = sum_j X[b][i][j] * v[b][j]; one wave per row.
-__global__ void __launch_bounds__(TPB) sm_pi_xv_kernel(const bf16_t* __restrict__ x, int rows, int cols, int ld,
-                                                       long long stride, const float* __restrict__ v,
-                                                       long long vstride, float* __restrict__ u, long long ustride) {
-  const int b = blockIdx.y;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= rows) return;
+__device__ __forceinline__ const sm_pi_desc& find_desc(const pi_args& a, int bx, int& local) {
+  int di = 0;
+  while (di + 1 < a.n && bx >= a.d[di + 1].block_begin) ++di;
+  local = bx - a.d[di].block_begin;
+  return a.d[di];
+}
+
+// 8 bf16 (one 16-byte load) times 8 floats
+__device__ __forceinline__ float dot8(const u32x4 x, const float* __restrict__ v) {
+  const f32x4 a = *reinterpret_cast<const f32x4*>(v), b = *reinterpret_cast<const f32x4*>(v + 4);
+  float s = 0.f;
+  s += __uint_as_float(x[0] << 16) * a[0];
+  s += __uint_as_float(x[0] & 0xFFFF0000u) * a[1];
+  s += __uint_as_float(x[1] << 16) * a[2];
+  s += __uint_as_float(x[1] & 0xFFFF0000u) * a[3];
+  s += __uint_as_float(x[2] << 16) * b[0];
+  s += __uint_as_float(x[2] & 0xFFFF0000u) * b[1];
+  s += __uint_as_float(x[3] << 16) * b[2];
+  s += __uint_as_float(x[3] & 0xFFFF0000u) * b[3];
+  return s;
+}
+
+// u[item][row] = sum_j X[item][row][j] v[item][j]: one wave per row, 16-byte loads, 4 rows per workgroup.
+__global__ void __launch_bounds__(TPB) sm_pi_xv_kernel(const pi_args a) {
+  int local;
+  const sm_pi_desc& D = find_desc(a, blockIdx.x, local);
+  const int rgroups = (D.rows + 3) / 4;
+  const int item = local / rgroups;
+  const int row = (local - item * rgroups) * 4 + (threadIdx.x >> 6);
+  if (row >= D.rows) return;
   const int lane = threadIdx.x & 63;
-  const bf16_t* xr = x + (long long)b * stride + (long long)row * ld;
-  const float* vb = v + (long long)b * vstride;
+  const bf16_t* xr = D.x + (long long)item * D.stride + (long long)row * D.ld;
+  const float* v = D.v + (long long)item * D.ld;
   float s = 0.f;
-  for (int j = lane; j < cols; j += 64) s += (float)xr[j] * vb[j];
+  for (int j = lane * 8; j < D.ld; j += 512) s += dot8(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xr + j)), v + j);
   s = wave_sum(s);
-  if (lane == 0) u[(long long)b * ustride + row] = s;
+  if (lane == 0) D.u[(long long)item * D.up + row] = s;
 }
 
-// v[b][j] = sum_i X[b][i][j] * u[b][i]; one thread per column.
-__global__ void __launch_bounds__(TPB) sm_pi_xtu_kernel(const bf16_t* __restrict__ x, int rows, int cols, int ld,
-                                                        long long stride, const float* __restrict__ u,
-                                                        long long ustride, float* __restrict__ v, long long vstride) {
-  const int b = blockIdx.y;
-  const int j = blockIdx.x * TPB + threadIdx.x;
-  if (j >= cols) return;
-  const bf16_t* xb = x + (long long)b * stride + j;
-  const float* ub = u + (long long)b * ustride;
-  float s = 0.f;
-  for (int i = 0; i < rows; ++i) s += (float)xb[(long long)i * ld] * ub[i];
-  v[(long long)b * vstride + j] = s;
+// part[item][chunk][j] = sum over the chunk's rows of X[item][i][j] u[item][i]: a workgroup owns a strip of
+// 512 columns and a chunk of SM_PI_ROW_CHUNK rows of one matrix; wave w takes rows w, w + 4, ... of the
+// chunk, a lane 8 columns; the four partial strips are added in wave order.  The chunks are added (in
+// order) by the normalisation that follows.
+__global__ void __launch_bounds__(TPB) sm_pi_xtu_kernel(const pi_args a) {
+  __shared__ float part[3][512];
+  int local;
+  const sm_pi_desc& D = find_desc(a, blockIdx.x, local);
+  const int strips = (D.ld + 511) / 512;
+  const int per_item = strips * D.chunks;
+  const int item = local / per_item;
+  const int rem = local - item * per_item;
+  const int chunk = rem / strips;
+  const int j0 = (rem - chunk * strips) * 512 + (threadIdx.x & 63) * 8;
+  const int wv = threadIdx.x >> 6;
+  const int r0 = chunk * SM_PI_ROW_CHUNK, r1 = min(D.rows, r0 + SM_PI_ROW_CHUNK);
+  const bf16_t* xb = D.x + (long long)item * D.stride + j0;
+  const float* u = D.u + (long long)item * D.up;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (j0 < D.ld) {
+#pragma unroll 4
+    for (int i = r0 + wv; i < r1; i += 4) {
+      const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xb + (long long)i * D.ld));
+      const float ui = u[i];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        acc[2 * q] += __uint_as_float(x[q] << 16) * ui;
+        acc[2 * q + 1] += __uint_as_float(x[q] & 0xFFFF0000u) * ui;
+      }
+    }
+  }
+  const int c = (threadIdx.x & 63) * 8;
+  if (wv > 0) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) part[wv - 1][c + k] = acc[k];
+  }
+  __syncthreads();
+  if (wv == 0 && j0 < D.ld) {
+    float* o = D.part + ((long long)item * D.chunks + chunk) * D.ld + j0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) o[k] = ((acc[k] + part[0][c + k]) + part[1][c + k]) + part[2][c + k];
+  }
 }
 
-// dst[b] = src[b] / (|src[b]| + eps) when dst != null; norm_out[b] = |src[b]| when non-null.
-__global__ void __launch_bounds__(TPB) sm_pi_normalize_kernel(const float* src, long long sstride, int n,
-                                                              float eps, float* dst, long long dstride,
-                                                              float* __restrict__ norm_out) {
+// One workgroup per matrix.  which = 0: v <- v0 / (|v0| + eps), zero-padded to ld.
+// which = 1: u <- u / (|u| + eps).  which = 2: v <- s / (|s| + eps) with s the sum of the row chunks'
+// partial X^T u.  which = 3: sigma = |u|.
+__global__ void __launch_bounds__(TPB) sm_pi_normalize_kernel(const pi_args a, int which) {
   __shared__ float red[4];
   __shared__ float nrm;
-  const int b = blockIdx.x;
-  const float* s = src + (long long)b * sstride;
+  int local;
+  const sm_pi_desc& D = find_desc(a, blockIdx.x, local);
+  const int item = local;
+  const float* src;
+  float* dst;
+  int n, n_out;
+  if (which == 0) {
+    src = D.v0 + (long long)item * D.v0_stride;
+    dst = D.v + (long long)item * D.ld;
+    n = D.cols;
+    n_out = D.ld;
+  } else if (which == 2) {
+    dst = D.v + (long long)item * D.ld;
+    const float* pp = D.part + (long long)item * D.chunks * D.ld;
+    for (int i = threadIdx.x; i < D.cols; i += TPB) {
+      float t = 0.f;
+      for (int ch = 0; ch < D.chunks; ++ch) t += pp[(long long)ch * D.ld + i];
+      dst[i] = t;
+    }
+    __syncthreads();
+    src = dst;
+    n = n_out = D.cols;
+  } else {
+    src = dst = D.u + (long long)item * D.up;
+    n = n_out = D.rows;
+  }
   float ss = 0.f;
-  for (int i = threadIdx.x; i < n; i += TPB) ss += s[i] * s[i];
+  for (int i = threadIdx.x; i < n; i += TPB) ss += src[i] * src[i];
   ss = wave_sum(ss);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
   __syncthreads();
   if (threadIdx.x == 0) {
     nrm = sqrtf((red[0] + red[1]) + (red[2] + red[3]));
-    if (norm_out) norm_out[b] = nrm;
+    if (which == 3) D.sigma[item] = nrm;
   }
   __syncthreads();
-  if (dst) {
-    const float inv = 1.0f / (nrm + eps);
-    float* d = dst + (long long)b * dstride;
-    for (int i = threadIdx.x; i < n; i += TPB) d[i] = s[i] * inv;
-  }
+  if (which == 3) return;
+  const float inv = 1.0f / (nrm + a.eps);
+  for (int i = threadIdx.x; i < n_out; i += TPB) dst[i] = (i < n) ? src[i] * inv : 0.f;
 }
 
 }  // namespace
 
-int sm_launch_power_iter(signmuon_ctx* ctx, const bf16_t* x, int rows, int cols, int ld, long long stride, int batch,
-                         int P, float eps, const float* v0, long long v0_stride, float* scratch, float* sigma) {
-  // scratch per batch item: u[rows], v[cols]
-  const long long per = (long long)rows + cols;
-  float* u = scratch;
-  float* v = scratch + rows;
-  sm_launch_scope sc(ctx, SM_K_OTHER);
-  auto normalize = [&](const float* s, long long ss, int n, float* d, long long ds, float* nout) {
-    hipLaunchKernelGGL(sm_pi_normalize_kernel, dim3(batch), dim3(TPB), 0, ctx->stream, s, ss, n, eps, d, ds, nout);
-  };
-  auto xv = [&]() {
-    hipLaunchKernelGGL(sm_pi_xv_kernel, dim3((rows + 3) / 4, batch), dim3(TPB), 0, ctx->stream, x, rows, cols, ld,
-                       stride, v, per, u, per);
-  };
-  auto xtu = [&]() {
-    hipLaunchKernelGGL(sm_pi_xtu_kernel, dim3((cols + TPB - 1) / TPB, batch), dim3(TPB), 0, ctx->stream, x, rows, cols,
-                       ld, stride, u, per, v, per);
-  };
-  normalize(v0, v0_stride, cols, v, per, nullptr);
-  for (int p = 0; p < P; ++p) {
-    xv();
-    normalize(u, per, rows, u, per, nullptr);
-    xtu();
-    normalize(v, per, cols, v, per, nullptr);
+int sm_launch_power_iter_group(signmuon_ctx* ctx, const sm_pi_desc* descs, int n, int P, float eps) {
+  int done = 0;
+  while (done < n) {
+    const int g = std::min(n - done, SM_PI_MAX_GROUP);
+    pi_args a_xv, a_xtu, a_nrm;
+    long long b_xv = 0, b_xtu = 0, b_nrm = 0;
+    for (pi_args* a : {&a_xv, &a_xtu, &a_nrm}) {
+      a->n = g;
+      a->P_unused = 0;
+      a->eps = eps;
+      a->pad_ = 0;
+    }
+    for (int i = 0; i < g; ++i) {
+      const sm_pi_desc& d = descs[done + i];
+      if (d.chunks != (d.rows + SM_PI_ROW_CHUNK - 1) / SM_PI_ROW_CHUNK) return sm_fail(ctx, SM_EINVAL, "internal: power iteration chunk count");
+      if (d.ld % 64 || d.up % 8 || d.up < d.rows || !sm_aligned(d.x, 16) || d.stride % 8 || !sm_aligned(d.v, 16))
+        return sm_fail(ctx, SM_EINVAL, "internal: power iteration operands not padded/aligned");
+      a_xv.d[i] = a_xtu.d[i] = a_nrm.d[i] = d;
+      a_xv.d[i].block_begin = (int)b_xv;
+      a_xtu.d[i].block_begin = (int)b_xtu;
+      a_nrm.d[i].block_begin = (int)b_nrm;
+      b_xv += (long long)((d.rows + 3) / 4) * d.items;
+      b_xtu += (long long)((d.ld + 511) / 512) * d.chunks * d.items;
+      b_nrm += d.items;
+    }
+    if (b_xv > 0x7FFFFFFFLL || b_xtu > 0x7FFFFFFFLL)
+      return sm_fail(ctx, SM_EUNSUPPORTED, "power iteration: too many rows for one launch");
+    if (b_nrm > 0) {
+      sm_launch_scope sc(ctx, SM_K_OTHER);
+      auto normalize = [&](int which) {
+        hipLaunchKernelGGL(sm_pi_normalize_kernel, dim3((unsigned)b_nrm), dim3(TPB), 0, ctx->stream, a_nrm, which);
+      };
+      auto xv = [&]() { hipLaunchKernelGGL(sm_pi_xv_kernel, dim3((unsigned)b_xv), dim3(TPB), 0, ctx->stream, a_xv); };
+      auto xtu = [&]() { hipLaunchKernelGGL(sm_pi_xtu_kernel, dim3((unsigned)b_xtu), dim3(TPB), 0, ctx->stream, a_xtu); };
+      normalize(0);
+      for (int p = 0; p < P; ++p) {
+        xv();
+        normalize(1);
+        xtu();
+        normalize(2);
+      }
+      xv();
+      normalize(3);
+    }
+    SM_HIP(ctx, hipGetLastError());
+    done += g;
   }
-  xv();
-  normalize(u, per, rows, nullptr, 0, sigma);
-  SM_HIP(ctx, hipGetLastError());
   return SM_OK;
 }
