@@ -67,9 +67,10 @@ def make_inputs(name, torch, device):
     return cfg, w, mom, grad
 
 
-def run_workload(name, steps, warmup, torch, P, B, scale="fro"):
+def run_workload(name, steps, warmup, torch, P, B, scale=None):
     device = torch.device("cuda:0")
     cfg, w, mom, grad = make_inputs(name, torch, device)
+    scale = scale or cfg.get("scale", "fro")
     shapes, M = cfg["shapes"], cfg["M"]
     K, Kp = cfg["ns_steps"], cfg["local_polar_steps"]
     ctx = P.Context()
@@ -138,7 +139,8 @@ def run_workload(name, steps, warmup, torch, P, B, scale="fro"):
     ms_vote = per_class[P.kernel_name(B.SM_K_VOTE)]["ms_per_step"]
     ms_mom = per_class[P.kernel_name(B.SM_K_MOMENTUM)]["ms_per_step"]
     res = {
-        "workload": name, "M": M, "n_blocks": len(shapes), "entries": d_total,
+        "workload": name, "M": M, "n_blocks": len(shapes), "entries": d_total, "ns_steps": K,
+        "local_polar_steps": Kp, "scale": scale,
         "steps_per_s": steps / elapsed, "ms_per_step": 1e3 * elapsed / steps,
         # nominal: the work of Alg. PolarNS as written (4 s^2 l per step and matrix) over the time of all
         # Newton-Schulz launches; executed: the matrix products actually launched
@@ -246,10 +248,11 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="nanogpt124m")
-    ap.add_argument("--also", default="resnet50", help="second workload reported in the same line ('' to skip)")
+    ap.add_argument("--also", default="resnet50,nanogpt_paper_k10,resnet50_k1",
+                    help="further workloads (comma separated) reported in the same line under 'also' ('' to skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--scale", default="fro", choices=["fro", "spectral"],
-                    help="scale of Alg. PolarNS: Frobenius norm (default) or PowerIter with P = 2")
+    ap.add_argument("--scale", default=None, choices=["fro", "spectral"],
+                    help="scale of Alg. PolarNS: Frobenius norm or PowerIter with P = 2 (default: the workload's own)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run three 1 GiB device copies (torch): a kernel of known traffic for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -274,9 +277,8 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
     main_res = run_workload(args.workload, args.steps, args.warmup, torch, P, B, scale=args.scale)
-    also = None
-    if args.also and args.also != args.workload:
-        also = run_workload(args.also, max(args.steps * 5, 50), args.warmup, torch, P, B)
+    also = [run_workload(nm, max(args.steps * 5, 50), args.warmup, torch, P, B)
+            for nm in args.also.split(",") if nm and nm != args.workload]
     # roofline of the dominant kernel: the GEMM class with the largest share of the step
     dom_name, dom = max(main_res["gemm"].items(), key=lambda kv: kv[1]["ms_per_step"])
     traffic = None
@@ -297,7 +299,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "M": main_res["M"], "blocks": main_res["n_blocks"],
-                   "entries": main_res["entries"], "ns_steps": 5, "scale": args.scale},
+                   "entries": main_res["entries"], "ns_steps": main_res["ns_steps"],
+                   "local_polar_steps": main_res["local_polar_steps"], "scale": main_res["scale"]},
         "roofline": {"kernel": dom_name, "bound": dom["bound"], "achieved": ach, "peak": peak, "unit": unit,
                      "frac": ach / peak, "traffic": traffic, "avg_launch_ms": dom["avg_launch_ms"],
                      "flop_per_launch": dom["flop_per_launch"], "bytes_per_launch": dom["bytes_per_launch"]},
@@ -317,9 +320,13 @@ def main():
         "workspace_GB": main_res["workspace_GB"],
     }
     if also:
-        line["also"] = {k: also[k] for k in ("workload", "M", "n_blocks", "steps_per_s", "ms_per_step", "ns_tflops",
-                                             "sign_vote_gbs", "momentum_gbs")}
-        line["also"]["per_class_ms"] = {k: round(v["ms_per_step"], 4) for k, v in also["per_class"].items()}
+        line["also"] = []
+        for a in also:
+            e = {k: a[k] for k in ("workload", "M", "n_blocks", "ns_steps", "local_polar_steps", "scale", "steps_per_s",
+                                   "ms_per_step", "ns_tflops", "ns_tflops_executed", "momentum_gbs")}
+            e["sign_vote_gbs"] = a["standalone"]["sign_vote_gbs"]
+            e["per_class_ms"] = {k: round(v["ms_per_step"], 4) for k, v in a["per_class"].items()}
+            line["also"].append(e)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(line))

@@ -39,6 +39,16 @@ WORKLOADS = {
     # int8 vote path
     "int8vote": dict(shapes=[(2048, 8192)] * 32, M=16, grad="normal", grad_std=1.0,
                      ns_steps=5, local_polar_steps=5, sign_fmt="int8", stream=5),
+    # The paper's own nanoGPT (6 layers, width 384) in its weak-scaling setting: 10 Newton-Schulz
+    # steps, spectral scale with 2 power iterations, update by the voted signs (no local polar step).
+    "nanogpt_paper_k10": dict(shapes=[(384, 1152), (384, 384), (384, 1536), (1536, 384)] * 6,
+                              M=8, grad="lowrank", grad_std=1.0, rank=8, scale="spectral",
+                              ns_steps=10, local_polar_steps=0, sign_fmt="1bit", stream=6),
+    # The ResNet-50-shaped set in the paper's best CIFAR-10 setting: one Newton-Schulz step, spectral scale.
+    "resnet50_k1": dict(shapes=[(64, 576), (128, 1152), (256, 2304), (512, 4608),
+                                (2048, 512), (1000, 2048)],
+                        M=4, grad="normal", grad_std=0.1, scale="spectral",
+                        ns_steps=1, local_polar_steps=0, sign_fmt="1bit", stream=7),
 }
 
 
