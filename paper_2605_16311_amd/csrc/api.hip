@@ -184,9 +184,11 @@ int launch_over_classes(signmuon_ctx* ctx, ns_plan* pl, const gemm_params& gp, i
         P[j].layout = 0;
         P[j].sign_out = nullptr;
         P[j].sign_stride = 0;
-        P[j].sign_rows = P[j].sign_cols = P[j].sign_fmt = P[j].pad_ = 0;
+        P[j].sign_rows = P[j].sign_cols = P[j].sign_fmt = P[j].mate = 0;
       }
       fill(pl->classes[c0 + i], P);
+      // problems of one class given together share operands: deal their tiles item by item
+      if (per_class == 2) P[0].mate = i * per_class + 1;
     }
     ga.n_prob = g * per_class;
     const int rc = sm_launch_gemm(ctx, ga, gp.sym, gp.klass);

@@ -191,7 +191,10 @@ struct sm_gemm_prob {
   long long sign_stride;
   int sign_rows, sign_cols;
   int sign_fmt;
-  int pad_;
+  // Index (> own index) of a second problem of equal M, N, K and batch whose tiles are dealt item by
+  // item right after this problem's (item b of this one, item b of the mate, item b + 1, ...), so
+  // that operands the two share are read from HBM once; 0 = none.  The mate owns no tiles itself.
+  int mate;
 };
 constexpr int SM_GEMM_MAX_PROB = 24;
 struct sm_gemm_args {

@@ -476,11 +476,17 @@ __global__ void __launch_bounds__(NTH) sm_ns_gemm_kernel(const sm_gemm_args args
     first_tile = false;
     int pi = 0;
     while (pi + 1 < args.n_prob && L >= args.p[pi + 1].tile_begin) ++pi;
+    int t = L - args.p[pi].tile_begin;
+    const int per_batch = SYM ? args.p[pi].tiles_m * (args.p[pi].tiles_m + 1) / 2 : args.p[pi].tiles_m * args.p[pi].tiles_n;
+    const int mate = args.p[pi].mate;
+    const int per_item = mate ? 2 * per_batch : per_batch;
+    const int b = t / per_item;
+    t -= b * per_item;
+    if (t >= per_batch) {  // the mate's tile of the same item
+      t -= per_batch;
+      pi = mate;
+    }
     const sm_gemm_prob& P = args.p[pi];
-    int t = L - P.tile_begin;
-    const int per_batch = SYM ? P.tiles_m * (P.tiles_m + 1) / 2 : P.tiles_m * P.tiles_n;
-    const int b = t / per_batch;
-    t -= b * per_batch;
     int tm, tn;
     if (SYM) {  // upper triangle, column by column: (0,0) (0,1) (1,1) (0,2) ...
       tn = 0;
@@ -516,12 +522,16 @@ static int fill_tiles(sm_gemm_args& args, bool sym, int ts) {
   constexpr double FIXED = 6.0;
   int total = 0;
   double cost = 0.0;
+  bool is_mate[SM_GEMM_MAX_PROB] = {};
+  for (int i = 0; i < args.n_prob; ++i)
+    if (args.p[i].mate) is_mate[args.p[i].mate] = true;
   for (int i = 0; i < args.n_prob; ++i) {
     sm_gemm_prob& P = args.p[i];
     P.tiles_m = (P.M + ts - 1) / ts;
     P.tiles_n = (P.N + ts - 1) / ts;
-    P.tile_begin = total;
-    const int n = (sym ? P.tiles_m * (P.tiles_m + 1) / 2 : P.tiles_m * P.tiles_n) * P.batch;
+    P.tile_begin = total;  // for a mate: the end of its leader's range, which the tile lookup steps over
+    if (is_mate[i]) continue;
+    const int n = (sym ? P.tiles_m * (P.tiles_m + 1) / 2 : P.tiles_m * P.tiles_n) * P.batch * (P.mate ? 2 : 1);
     total += n;
     cost += n * (P.K / 64 + FIXED);
   }
@@ -531,7 +541,7 @@ static int fill_tiles(sm_gemm_args& args, bool sym, int ts) {
   double done = 0.0;  // cost of the problems before pi
   while (x < 8 && pi < args.n_prob) {
     const sm_gemm_prob& P = args.p[pi];
-    const int end = (pi + 1 < args.n_prob) ? args.p[pi + 1].tile_begin : total;
+    const int end = (pi + 1 < args.n_prob) ? args.p[pi + 1].tile_begin : total;  // == tile_begin for a mate
     const double per_tile = P.K / 64 + FIXED, target = cost * x / 8;
     const double here = done + (double)(end - P.tile_begin) * per_tile;
     if (here < target) {
@@ -566,6 +576,12 @@ int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, bool sym, int klass) {
       return sm_fail(ctx, SM_EUNSUPPORTED, "internal: GEMM layout combination not built");
     if (!sm_aligned(P.R, 16)) return sm_fail(ctx, SM_EINVAL, "internal: GEMM R term misaligned");
     if (!P.C && (sym || !P.sign_out)) return sm_fail(ctx, SM_EINVAL, "internal: GEMM without an output");
+    if (P.mate) {
+      if (P.mate <= i || P.mate >= args.n_prob) return sm_fail(ctx, SM_EINVAL, "internal: GEMM mate index");
+      const sm_gemm_prob& Q = args.p[P.mate];
+      if (Q.mate || Q.M != P.M || Q.N != P.N || Q.K != P.K || Q.batch != P.batch)
+        return sm_fail(ctx, SM_EINVAL, "internal: GEMM mate of a different shape");
+    }
     if (P.sign_out && (sym || args.out_f16 || P.R || P.sign_cols % 32 || P.sign_stride % 8 || !sm_aligned(P.sign_out, 8) ||
                        (P.sign_fmt != SM_SIGN_1BIT && P.sign_fmt != SM_SIGN_INT8)))
       return sm_fail(ctx, SM_EUNSUPPORTED, "internal: GEMM sign output needs a general bf16 product and cols % 32 == 0");
