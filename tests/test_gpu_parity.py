@@ -216,6 +216,39 @@ def test_vote_int8_sixteen_entry_groups(P, ctx, M, n):
     assert np.array_equal(gv[:n], vote_ref.astype(np.float32)) and np.all(gv[n:] == 5.0)
 
 
+@pytest.mark.parametrize("snr", [0.25, 1.0])
+def test_majority_vote_sign_error_falls_like_inverse_sqrt_m(P, ctx, snr):
+    """Lemma "Majority vote improves sign reliability": with M independent workers whose gradient entries are
+    g + sigma z (symmetric unimodal noise), the vote's sign-error rate is at most sigma / (sqrt(M) |g|).  The
+    library's pack + vote on synthetic entries: the measured rate matches the exact binomial value (ties -> +1),
+    obeys the bound and falls with M."""
+    from scipy import stats
+    n = 1 << 20
+    g = np.where(np.arange(n) % 2 == 0, snr, -snr).astype(np.float32)      # sigma = 1
+    prev = 1.0
+    p1 = float(stats.norm.cdf(-snr))                                       # one worker's failure probability
+    for M in (1, 4, 16, 64):
+        z = wl.normal((M, n), stream=32, block=M, worker=int(snr * 100))
+        u = dev((g[None, :] + z).astype(np.float32))
+        stride = O.packed_stride_bytes(n)
+        bits = torch.zeros((M, stride), dtype=torch.uint8, device="cuda")
+        P.signmuon_sign_pack(ctx, u, "1bit", bits)
+        v8 = torch.zeros((n,), dtype=torch.int8, device="cuda")
+        P.signmuon_majority_vote(ctx, bits, "1bit", M, n, stride, voted=v8, vfmt="int8")
+        vote = v8.cpu().numpy()
+        fail = float(np.mean(vote != np.sign(g)))
+        # exact: entries with g > 0 fail iff fewer than M/2 workers are right; with g < 0 a tie also fails
+        k = np.arange(M + 1)
+        pmf = stats.binom.pmf(k, M, 1.0 - p1)                              # number of correct workers
+        q_pos = pmf[2 * k < M].sum()
+        q_neg = pmf[2 * k <= M].sum()
+        q = 0.5 * (q_pos + q_neg)
+        assert abs(fail - q) <= 5.0 * np.sqrt(q * (1 - q) / n) + 1e-6, (M, fail, q)
+        assert fail <= 1.0 / (np.sqrt(M) * snr) + 1e-3, (M, fail)
+        assert fail < prev or M == 1
+        prev = fail
+
+
 def test_vote_ignores_garbage_tail_bits_and_dropped_worker(P, ctx):
     M, n = 5, 70
     rng = wl.rng_for(25)
