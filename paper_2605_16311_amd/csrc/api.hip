@@ -50,7 +50,6 @@ void sm_plan_free(signmuon_ctx* ctx) {
   ctx->plan = nullptr;
 }
 
-int sm_launch_fill(signmuon_ctx* ctx, float* p, int n, float v);  // stream.hip
 
 namespace {
 
@@ -484,6 +483,27 @@ int spectral_sigma(signmuon_ctx* ctx, ns_plan* pl, int buf, int items, int items
   return sm_launch_power_iter_group(ctx, d.data(), n, P, eps);
 }
 
+// inv = 1 / max(sigma, eps) for `items` matrices per block of every class, in one launch.
+// mode 0: sigma from the momentum kernel's partial sums of squares; 1: sigma as left by PowerIter;
+// 2: the Frobenius norm of a +-1 matrix, sqrt(rows * cols), known in closed form.
+int class_inv_sigma(signmuon_ctx* ctx, ns_plan* pl, int items, int mode, float eps) {
+  std::vector<sm_sigma_desc> d;
+  for (auto& cl : pl->classes) {
+    sm_sigma_desc D;
+    D.partial = at<float>(ctx, cl.off_partial);
+    D.sig = at<float>(ctx, cl.off_sig);
+    D.inv = at<float>(ctx, cl.off_inv);
+    D.chunks = cl.chunks;
+    D.count = cl.count * items;
+    D.mode = mode;
+    D.value = 1.0f / fmaxf(sqrtf((float)cl.rows * (float)cl.cols), eps);
+    D.block_begin = 0;
+    D.pad_ = 0;
+    d.push_back(D);
+  }
+  return sm_launch_sigma_group(ctx, d.data(), (int)d.size(), eps);
+}
+
 bool bad_coeffs(const float* c) { return !c || !isfinite(c[0]) || !isfinite(c[1]) || !isfinite(c[2]); }
 
 }  // namespace
@@ -680,21 +700,14 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
   bool use_scale = false;
   if (s->ns_steps > 0 || (s->u_out != nullptr)) {
     if (s->scale == SM_SCALE_FRO) {
-      for (auto& cl : pl->classes) {
-        rc = sm_launch_reduce_partials(ctx, at<float>(ctx, cl.off_partial), cl.chunks, cl.count * M,
-                                       at<float>(ctx, cl.off_sig));
-        if (rc != SM_OK) return rc;
-        rc = sm_launch_inv_sigma(ctx, at<float>(ctx, cl.off_sig), cl.count * M, s->eps, true, at<float>(ctx, cl.off_inv));
-        if (rc != SM_OK) return rc;
-      }
+      rc = class_inv_sigma(ctx, pl, M, 0, s->eps);
+      if (rc != SM_OK) return rc;
       use_scale = true;
     } else if (spectral) {
       rc = spectral_sigma(ctx, pl, 0, M, M, s->v0, s->power_iters, s->eps);
       if (rc != SM_OK) return rc;
-      for (auto& cl : pl->classes) {
-        rc = sm_launch_inv_sigma(ctx, at<float>(ctx, cl.off_sig), cl.count * M, s->eps, false, at<float>(ctx, cl.off_inv));
-        if (rc != SM_OK) return rc;
-      }
+      rc = class_inv_sigma(ctx, pl, M, 1, s->eps);
+      if (rc != SM_OK) return rc;
       use_scale = true;
     }
   }
@@ -798,21 +811,16 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
   // a7: local polar step on the voted sign matrices (one per block)
   bool use_scale2 = false;
   if (s->scale == SM_SCALE_FRO) {
-    for (auto& cl : pl->classes) {
-      // every entry is +-1, so the Frobenius norm is exactly sqrt(rows*cols)
-      const float sig = sqrtf((float)cl.rows * (float)cl.cols);
-      rc = sm_launch_fill(ctx, at<float>(ctx, cl.off_inv), cl.count, 1.0f / fmaxf(sig, s->eps));
-      if (rc != SM_OK) return rc;
-    }
+    // every entry is +-1, so the Frobenius norm is exactly sqrt(rows*cols)
+    rc = class_inv_sigma(ctx, pl, 1, 2, s->eps);
+    if (rc != SM_OK) return rc;
     use_scale2 = true;
   } else if (spectral) {
     // worker 0's start vector serves the voted matrix of each block
     rc = spectral_sigma(ctx, pl, cur ^ 1, 1, 1, s->v0, s->power_iters, s->eps);
     if (rc != SM_OK) return rc;
-    for (auto& cl : pl->classes) {
-      rc = sm_launch_inv_sigma(ctx, at<float>(ctx, cl.off_sig), cl.count, s->eps, false, at<float>(ctx, cl.off_inv));
-      if (rc != SM_OK) return rc;
-    }
+    rc = class_inv_sigma(ctx, pl, 1, 1, s->eps);
+    if (rc != SM_OK) return rc;
     use_scale2 = true;
   }
   cur ^= 1;

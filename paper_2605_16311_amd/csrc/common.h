@@ -89,6 +89,20 @@ int sm_launch_momentum(signmuon_ctx* ctx, const sm_mom_desc* descs, int n, int M
 int sm_launch_reduce_partials(signmuon_ctx* ctx, const float* partial, int chunks, int count, float* sumsq);
 // inv_sigma[i] = 1 / max(sqrt(sumsq[i]), eps)   (from_sq) or 1 / max(sumsq[i], eps)
 int sm_launch_inv_sigma(signmuon_ctx* ctx, const float* sig, int count, float eps, bool from_sq, float* inv_sigma);
+// Grouped form over a table of matrix classes, one launch: per class `count` items with
+//   mode 0: sig = sum of the item's `chunks` partial sums of squares, inv = 1 / max(sqrt(sig), eps)
+//   mode 1: inv = 1 / max(sig, eps)          mode 2: inv = value
+struct sm_sigma_desc {
+  const float* partial;
+  float* sig;
+  float* inv;
+  int chunks, count, mode;
+  float value;
+  int block_begin;  // filled by the launcher
+  int pad_;
+};
+constexpr int SM_SIGMA_MAX_GROUP = 64;
+int sm_launch_sigma_group(signmuon_ctx* ctx, const sm_sigma_desc* descs, int n, float eps);
 
 // Grouped sign pack: one launch over a table of matrices, `M` workers each.
 struct sm_sp_desc {

@@ -124,9 +124,31 @@ __global__ void sm_inv_sigma_kernel(const float* sig, int count, float eps, int 
   inv[i] = 1.0f / fmaxf(s, eps);
 }
 
-__global__ void sm_fill_kernel(float* p, int n, float v) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = v;
+struct sigma_args {
+  int n;
+  float eps;
+  sm_sigma_desc d[SM_SIGMA_MAX_GROUP];
+};
+
+// One workgroup per item of every class of the table.
+__global__ void __launch_bounds__(TPB) sm_sigma_group_kernel(const sigma_args a) {
+  __shared__ float red[4];
+  int di = 0;
+  while (di + 1 < a.n && (int)blockIdx.x >= a.d[di + 1].block_begin) ++di;
+  const sm_sigma_desc& D = a.d[di];
+  const int i = blockIdx.x - D.block_begin;
+  if (D.mode == 0) {
+    const float* src = D.partial + (long long)i * D.chunks;
+    float s = 0.f;
+    for (int j = threadIdx.x; j < D.chunks; j += TPB) s += src[j];
+    const float tot = block_sum(s, red);
+    if (threadIdx.x == 0) {
+      D.sig[i] = tot;
+      D.inv[i] = 1.0f / fmaxf(sqrtf(tot), a.eps);
+    }
+  } else if (threadIdx.x == 0) {
+    D.inv[i] = (D.mode == 1) ? 1.0f / fmaxf(D.sig[i], a.eps) : D.value;
+  }
 }
 
 // ------------------------------------------------------------------ sign pack
@@ -479,10 +501,26 @@ int sm_launch_inv_sigma(signmuon_ctx* ctx, const float* sig, int count, float ep
   return SM_OK;
 }
 
-int sm_launch_fill(signmuon_ctx* ctx, float* p, int n, float v) {
-  sm_launch_scope sc(ctx, SM_K_OTHER);
-  hipLaunchKernelGGL(sm_fill_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, p, n, v);
-  SM_HIP(ctx, hipGetLastError());
+int sm_launch_sigma_group(signmuon_ctx* ctx, const sm_sigma_desc* descs, int n, float eps) {
+  int done = 0;
+  while (done < n) {
+    const int g = std::min(n - done, SM_SIGMA_MAX_GROUP);
+    sigma_args a;
+    a.n = g;
+    a.eps = eps;
+    int blocks = 0;
+    for (int i = 0; i < g; ++i) {
+      a.d[i] = descs[done + i];
+      a.d[i].block_begin = blocks;
+      blocks += a.d[i].count;
+    }
+    if (blocks > 0) {
+      sm_launch_scope sc(ctx, SM_K_OTHER);
+      hipLaunchKernelGGL(sm_sigma_group_kernel, dim3(blocks), dim3(TPB), 0, ctx->stream, a);
+    }
+    SM_HIP(ctx, hipGetLastError());
+    done += g;
+  }
   return SM_OK;
 }
 
