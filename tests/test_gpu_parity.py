@@ -418,6 +418,48 @@ def test_step_signs_written_by_the_apply_alone(P, ctx):
             assert np.array_equal(x.view(np.uint8), y.view(np.uint8))
 
 
+def test_step_replays_from_a_hip_graph(P):
+    """After the first call (which plans and clears the workspace) a step only enqueues kernels on the
+    context's stream, so it can be captured once and replayed.  Four replays, with eager work and
+    synchronisations between them, must leave W and the momentum bit-identical to four eager steps."""
+    shapes, M = [(128, 256), (256, 128), (192, 192), (64, 100)], 3
+
+    def fresh():
+        w = [dev(wl.weights(r, c, block=i, stream=33)) for i, (r, c) in enumerate(shapes)]
+        mom = [torch.zeros((M, r, c), device="cuda") for r, c in shapes]
+        grad = [dev(wl.normal((M, r, c), stream=33, block=i)) for i, (r, c) in enumerate(shapes)]
+        return w, mom, grad
+
+    results = []
+    for use_graph in (False, True):
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            w, mom, grad = fresh()
+            ctx = P.Context(stream=side)
+            plan = P.StepPlan(w, mom, grad, beta=0.9, lr=1e-2, ns_steps=5, sign_fmt="1bit", local_polar_steps=3)
+            P.signmuon_step(ctx, plan)                      # plans the workspace
+            side.synchronize()
+            snaps = []
+            if use_graph:
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=side):
+                    P.signmuon_step(ctx, plan)
+            for rep in range(4):
+                if use_graph:
+                    graph.replay()
+                else:
+                    P.signmuon_step(ctx, plan)
+                torch.cuda.synchronize()
+                scratch = torch.randn((1 << 16,), device="cuda").sum().item()      # unrelated eager work between replays
+                assert np.isfinite(scratch)
+                snaps.append(([t.cpu().numpy().copy() for t in w], [t.cpu().numpy().copy() for t in mom]))
+            ctx.close()
+        results.append(snaps)
+    for rep in range(4):
+        for a, b in zip(results[0][rep][0] + results[0][rep][1], results[1][rep][0] + results[1][rep][1]):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), f"replay {rep}"
+
+
 def test_step_spectral(P, ctx):
     run_step_case(P, ctx, [(128, 256), (256, 128)], 2, sign_fmt="1bit", Kp=2, scale="spectral")
 
