@@ -391,14 +391,17 @@ def test_step_single256(P, ctx):
 @pytest.mark.parametrize("sign_fmt", ["1bit", "int8"])
 @pytest.mark.parametrize("Kp", [0, 3])
 def test_step_mixed_set(P, ctx, sign_fmt, Kp):
-    shapes = [(64, 192), (192, 64), (64, 192), (128, 128), (100, 72), (64, 192)]
+    # (200, 160) and (96, 224): signs packed by the apply GEMM with zero padding in both dimensions;
+    # (100, 72): rows that do not pack into whole words (separate sign-pack launch)
+    shapes = [(64, 192), (192, 64), (64, 192), (128, 128), (100, 72), (64, 192), (200, 160), (96, 224)]
     run_step_case(P, ctx, shapes, 3, sign_fmt=sign_fmt, Kp=Kp, wd=0.1, rsqrt=(Kp > 0))
 
 
 def test_step_signs_written_by_the_apply_alone(P, ctx):
     """Without a u_out tap the last apply writes only the packed signs (U is never stored).  The same step
     with all taps (checked against the oracle by the cases above) must give the same signs, counts and W."""
-    shapes, M = [(128, 256), (256, 128), (192, 192), (64, 100)], 3      # the last one cannot be packed by the GEMM
+    # (64, 100) cannot be packed by the GEMM; (200, 160) is packed with padding in both dimensions
+    shapes, M = [(128, 256), (256, 128), (192, 192), (64, 100), (200, 160)], 3
     outs = []
     for tapped in (True, False):
         w = [dev(wl.weights(r, c, block=i)) for i, (r, c) in enumerate(shapes)]
