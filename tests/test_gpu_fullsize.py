@@ -107,17 +107,8 @@ def test_resnet50_step_in_bench_configuration(P):
 
 
 def progress(msg):
-    """Progress line for the multi-minute tests: printed, and appended to a log next to the other GPU-run
-    output so that a watcher of that folder sees the test advancing while pytest captures stdout."""
+    """Progress line of the minute-long tests (visible with pytest -s)."""
     print(msg, flush=True)
-    try:
-        import os
-        out = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-        os.makedirs(out, exist_ok=True)
-        with open(os.path.join(out, "fullsize_progress.log"), "a") as f:
-            f.write(msg + "\n")
-    except OSError:
-        pass
 
 
 def streamed_full_step_check(P, name, ns_items, mom_workers):
