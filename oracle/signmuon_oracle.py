@@ -211,6 +211,17 @@ def local_polar(S_bar, steps, coeffs=PAPER_COEFFS, scale="fro", power_iters=2,
     return polar_ns(S, steps, coeffs, scale, power_iters, eps, v0, dtype)
 
 
+def normalized_sign(S_bar, power_iters, eps, v0, dtype=np.float64):
+    """The "normalized sign" direction D = S-bar / ||S-bar||_op of the appendix "Spectral
+    normalization and polar decomposition are local", with the operator norm estimated by
+    Alg. PowerIter from the start vector v0: D = kappa S-bar, kappa = 1 / max(sigma, eps)."""
+    T = np.dtype(dtype).type
+    S = np.asarray(S_bar, dtype=dtype)
+    sigma = power_iter(S, power_iters, eps, np.asarray(v0, dtype=dtype))
+    kappa = T(1.0) / max(T(sigma), T(eps))
+    return kappa * S
+
+
 def apply_update(W, D, lr, rsqrt_mn=False, dtype=np.float64):
     """W <- W - eta * kappa * D, kappa = 1/sqrt(mn) if rsqrt_mn else 1.
     The step eta*kappa is formed first (in `dtype`), then one multiply and
@@ -230,7 +241,7 @@ def apply_update(W, D, lr, rsqrt_mn=False, dtype=np.float64):
 def signmuon_step(W, mom, grad, *, beta, weight_decay=0.0, lr, ns_steps,
                   coeffs=PAPER_COEFFS, scale="fro", power_iters=2, eps=1e-12,
                   v0=None, sign_fmt="1bit", local_polar_steps=0,
-                  rsqrt_mn=False, dtype=np.float64):
+                  rsqrt_mn=False, op_norm=False, dtype=np.float64):
     """One Sign-Muon iteration on one block.  W: [r, c]; mom, grad: [M, r, c];
     v0: [M, c] or None.  Returns dict with the new W and momentum and every
     intermediate (U, packed/int8 signs, counts, vote, D)."""
@@ -250,8 +261,13 @@ def signmuon_step(W, mom, grad, *, beta, weight_decay=0.0, lr, ns_steps,
     else:
         raise ValueError(sign_fmt)
     S_bar = vote.reshape(r, c)
-    D = local_polar(S_bar, local_polar_steps, coeffs, scale, power_iters, eps,
-                    None if v0 is None else v0[0], dtype)
+    if op_norm:
+        if local_polar_steps > 0 or rsqrt_mn:
+            raise ValueError("op_norm shapes the voted sign itself: no local polar step, no 1/sqrt(mn)")
+        D = normalized_sign(S_bar, power_iters, eps, v0[0], dtype)
+    else:
+        D = local_polar(S_bar, local_polar_steps, coeffs, scale, power_iters, eps,
+                        None if v0 is None else v0[0], dtype)
     new_W = apply_update(W, D, lr, rsqrt_mn, dtype)
     return dict(W=new_W, mom=new_mom, U=U, signs=signs, counts=counts,
                 vote=S_bar, D=D)

@@ -344,3 +344,44 @@ def test_float32_variant_tracks_float64():
     b = O.polar_ns(X, 5, dtype=np.float64)
     assert a.dtype == np.float32
     assert np.linalg.norm(a - b) / np.linalg.norm(b) < 1e-5
+
+
+# ---------------------------------------------------------------- P14: normalized sign (operator-norm scaling)
+def test_normalized_sign_of_rank_one_sign_matrix_is_exact():
+    """S = x y^T with x, y in {-1, +1}: ||S||_op = sqrt(rc) exactly, reached by PowerIter from any start
+    vector not orthogonal to y, so D = S / sqrt(rc) -- the paper's "safe upper bound" form is then tight."""
+    rng = np.random.default_rng(5)
+    r, c = 12, 20
+    x = rng.choice([-1.0, 1.0], size=r)
+    y = rng.choice([-1.0, 1.0], size=c)
+    S = np.outer(x, y)
+    D = O.normalized_sign(S, 2, 1e-12, rng.standard_normal(c) + 3.0 * y)
+    assert np.allclose(D, S / np.sqrt(r * c), rtol=1e-12, atol=0)
+
+
+def test_normalized_sign_has_operator_norm_at_least_one_and_near_one():
+    """PowerIter never overestimates ||S||_op (it is a Rayleigh quotient), so ||D||_op >= 1, and after a few
+    iterations on a generic +-1 matrix it is within a few percent of 1; the Frobenius bound sqrt(rc) is looser."""
+    rng = np.random.default_rng(6)
+    r, c = 40, 64
+    S = rng.choice([-1.0, 1.0], size=(r, c))
+    true = np.linalg.svd(S, compute_uv=False)[0]
+    for P in (0, 2, 8):
+        D = O.normalized_sign(S, P, 1e-12, rng.standard_normal(c))
+        op = np.linalg.svd(D, compute_uv=False)[0]
+        assert op >= 1.0 - 1e-12
+        if P == 8:
+            assert op <= 1.1
+    assert true <= np.sqrt(r * c)
+
+
+def test_step_with_normalized_sign_moves_every_entry_by_the_same_amount():
+    rng = np.random.default_rng(7)
+    M, r, c = 3, 8, 12
+    W = rng.standard_normal((r, c))
+    G = rng.standard_normal((M, r, c))
+    v0 = rng.standard_normal((M, c))
+    out = O.signmuon_step(W, np.zeros_like(G), G, beta=0.9, lr=0.1, ns_steps=3, v0=v0, power_iters=2, op_norm=True)
+    sigma = O.power_iter(out["vote"].astype(np.float64), 2, 1e-12, v0[0])
+    assert np.allclose(np.abs(W - out["W"]), 0.1 / sigma, rtol=1e-12)
+    assert np.array_equal(np.sign(W - out["W"]), out["vote"])
