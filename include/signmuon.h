@@ -151,14 +151,19 @@ typedef struct signmuon_step_args {
                                 The local polar step uses worker 0's vector. */
   int32_t sign_fmt;          /* SM_SIGN_1BIT or SM_SIGN_INT8 */
   int32_t local_polar_steps; /* K' >= 0; 0: D = voted sign */
-  int32_t update_rsqrt_mn;   /* 1: step = lr / sqrt(rows*cols) (eq. signmuon_update) */
+  int32_t update_rsqrt_mn;   /* scale kappa of the update W <- W - lr kappa D:
+                                0: 1 (Alg. 2);  1: 1 / sqrt(rows*cols) (eq. signmuon_update);
+                                2: 1 / max(sigma, eps), sigma = PowerIter(voted sign, power_iters, eps,
+                                   worker 0's v0): the "normalized sign" D = S / ||S||_op of the
+                                   appendix; needs v0 and local_polar_steps == 0 */
   int32_t reserved;
   /* optional taps, arrays may be NULL and so may single entries */
   void* const* signs_out;     /* [n_mats] -> per-worker signs, M rows of
                                  8*ceil(d/64) bytes (1-bit) or d bytes (int8) */
   int32_t* const* counts_out; /* [n_mats] -> int32 [d] */
   void* const* u_out;         /* [n_mats] -> bf16 [M][rows][cols]: PolarNS output before the sign */
-  void* const* d_out;         /* [n_mats] -> bf16 [rows][cols]: update direction D */
+  void* const* d_out;         /* [n_mats] -> bf16 [rows][cols]: update direction D (the voted sign itself
+                                 when update_rsqrt_mn == 2: its scale is a scalar) */
 } signmuon_step_args;
 
 int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* args);

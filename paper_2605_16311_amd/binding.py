@@ -224,7 +224,8 @@ class StepPlan:
         a.coeffs = (C.c_float * 3)(*coeffs)
         a.ns_steps, a.scale, a.power_iters = ns_steps, SCALES[scale], power_iters
         a.sign_fmt, a.local_polar_steps = SIGN_FMTS[sign_fmt], local_polar_steps
-        a.update_rsqrt_mn, a.reserved = int(update_rsqrt_mn), 0
+        # 0 / False: kappa = 1; 1 / True: 1 / sqrt(rows * cols); 2 or "op_norm": 1 / PowerIter(voted sign)
+        a.update_rsqrt_mn, a.reserved = (2 if update_rsqrt_mn == "op_norm" else int(update_rsqrt_mn)), 0
         self.args = a
 
 

@@ -659,13 +659,17 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
   if (!(s->eps >= 0.f)) return sm_fail(ctx, SM_EINVAL, "step: eps must be >= 0");
   const bool spectral = (s->scale == SM_SCALE_SPECTRAL);
   if (spectral && (!s->v0 || s->power_iters < 0)) return sm_fail(ctx, SM_EINVAL, "step: spectral scale needs v0");
+  if (s->update_rsqrt_mn < 0 || s->update_rsqrt_mn > 2) return sm_fail(ctx, SM_EINVAL, "step: bad update scale mode");
+  const bool op_norm = (s->update_rsqrt_mn == 2);
+  if (op_norm && (!s->v0 || s->power_iters < 0 || s->local_polar_steps != 0))
+    return sm_fail(ctx, SM_EINVAL, "step: the normalized-sign update needs v0 and no local polar step");
   const int n = s->n_mats, M = s->M;
   for (int i = 0; i < n; ++i) {
     if (s->rows[i] < 1 || s->cols[i] < 1) return sm_fail(ctx, SM_EINVAL, "step: bad block shape");
     if (!s->w[i] || !s->mom[i] || !s->grad[i]) return sm_fail(ctx, SM_EINVAL, "step: NULL block pointer");
     if (!sm_aligned(s->w[i], 16) || !sm_aligned(s->mom[i], 16) || !sm_aligned(s->grad[i], 16))
       return sm_fail(ctx, SM_EINVAL, "step: block pointers need 16-byte alignment");
-    if (spectral && !s->v0[i]) return sm_fail(ctx, SM_EINVAL, "step: NULL v0 entry");
+    if ((spectral || op_norm) && !s->v0[i]) return sm_fail(ctx, SM_EINVAL, "step: NULL v0 entry");
     if (s->signs_out && s->signs_out[i] && !sm_aligned(s->signs_out[i], 16))
       return sm_fail(ctx, SM_EINVAL, "step: signs_out needs 16-byte alignment");
     if (s->counts_out && s->counts_out[i] && !sm_aligned(s->counts_out[i], 16))
@@ -763,7 +767,7 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
       sp.push_back(S);
     }
     float step = s->lr;
-    if (s->update_rsqrt_mn) step = s->lr / sqrtf((float)cl.rows * (float)cl.cols);
+    if (s->update_rsqrt_mn == 1) step = s->lr / sqrtf((float)cl.rows * (float)cl.cols);
     sm_vote_desc& V = vd[i];
     V.signs = signs;
     V.n = d;
@@ -772,7 +776,7 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
     V.lr = step;
     V.M = M;
     V.block_begin = 0;
-    if (Kp == 0) {
+    if (Kp == 0 && !op_norm) {
       V.voted = nullptr;
       V.vfmt = SM_VOTE_BF16;
       V.cols = V.ld = 1;
@@ -793,7 +797,7 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
   }
   rc = sm_launch_vote_group(ctx, vd.data(), n, s->sign_fmt);
   if (rc != SM_OK) return rc;
-  if (Kp == 0 && s->d_out) {  // W was already stepped; the tap only re-derives the vote
+  if (Kp == 0 && !op_norm && s->d_out) {  // W was already stepped; the tap only re-derives the vote
     for (int i = 0; i < n; ++i) {
       if (!s->d_out[i]) continue;
       sm_vote_desc t = vd[i];
@@ -806,17 +810,22 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
       if (rc != SM_OK) return rc;
     }
   }
-  if (Kp == 0) return SM_OK;
+  if (Kp == 0 && !op_norm) return SM_OK;
 
-  // a7: local polar step on the voted sign matrices (one per block)
+  // a7: local polar step on the voted sign matrices (one per block), or their operator norm for
+  // the normalized-sign update (worker 0's start vector serves the voted matrix of each block)
   bool use_scale2 = false;
-  if (s->scale == SM_SCALE_FRO) {
+  if (op_norm) {
+    rc = spectral_sigma(ctx, pl, cur ^ 1, 1, 1, s->v0, s->power_iters, s->eps);
+    if (rc != SM_OK) return rc;
+    rc = class_inv_sigma(ctx, pl, 1, 1, s->eps);
+    if (rc != SM_OK) return rc;
+  } else if (s->scale == SM_SCALE_FRO) {
     // every entry is +-1, so the Frobenius norm is exactly sqrt(rows*cols)
     rc = class_inv_sigma(ctx, pl, 1, 2, s->eps);
     if (rc != SM_OK) return rc;
     use_scale2 = true;
   } else if (spectral) {
-    // worker 0's start vector serves the voted matrix of each block
     rc = spectral_sigma(ctx, pl, cur ^ 1, 1, 1, s->v0, s->power_iters, s->eps);
     if (rc != SM_OK) return rc;
     rc = class_inv_sigma(ctx, pl, 1, 1, s->eps);
@@ -834,9 +843,10 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
     const int idx = pl->index_in_class[i];
     const bf16_t* dmat = at<bf16_t>(ctx, cl.off_x[cur]) + (long long)idx * cl.mat;
     float step = s->lr;
-    if (s->update_rsqrt_mn) step = s->lr / sqrtf((float)cl.rows * (float)cl.cols);
+    if (s->update_rsqrt_mn == 1) step = s->lr / sqrtf((float)cl.rows * (float)cl.cols);
     ud[i].w = s->w[i];
     ud[i].d = dmat;
+    ud[i].kappa = op_norm ? at<float>(ctx, cl.off_inv) + idx : nullptr;
     ud[i].rows = cl.rows;
     ud[i].cols = cl.cols;
     ud[i].ld = cl.cp;

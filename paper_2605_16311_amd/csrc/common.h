@@ -136,6 +136,7 @@ int sm_launch_vote_group(signmuon_ctx* ctx, const sm_vote_desc* descs, int n, in
 struct sm_upd_desc {
   float* w;
   const bf16_t* d;
+  const float* kappa;  // optional device scalar multiplied into step
   int rows, cols, ld;
   float step;
   int block_begin;   // filled by the launcher

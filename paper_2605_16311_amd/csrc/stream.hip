@@ -427,7 +427,7 @@ __global__ void __launch_bounds__(TPB) sm_update_kernel(const upd_args g) {
   float* __restrict__ w = D.w;
   const bf16_t* __restrict__ d = D.d;
   const int cols = D.cols, ld = D.ld;
-  const float step = D.step;
+  const float step = D.kappa ? __fmul_rn(D.step, D.kappa[0]) : D.step;
   const long long n = (long long)D.rows * cols;
   const long long e0 = ((long long)(blockIdx.x - D.block_begin) * TPB + threadIdx.x) * 4;
   if (e0 >= n) return;
@@ -859,6 +859,7 @@ int sm_launch_update(signmuon_ctx* ctx, float* w, const bf16_t* d, int rows, int
   D.rows = rows;
   D.cols = cols;
   D.ld = ld;
+  D.kappa = nullptr;
   D.step = step;
   D.block_begin = 0;
   D.pad_ = 0;

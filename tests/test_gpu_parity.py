@@ -463,6 +463,38 @@ def test_step_replays_from_a_hip_graph(P):
             assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), f"replay {rep}"
 
 
+def test_step_with_normalized_sign_update(P, ctx):
+    """update scale mode 2: W <- W - lr S / max(PowerIter(S), eps) with S the voted sign (the appendix's
+    "normalized sign").  The vote is checked bit-exactly from the GPU's own U; the step size, which every entry
+    of a block shares, against the float32 oracle's PowerIter on the same S and start vector."""
+    shapes, M, lr = [(128, 256), (200, 160), (64, 100), (256, 128)], 3, 0.05
+    W0 = [wl.weights(r, c, block=i, stream=34) for i, (r, c) in enumerate(shapes)]
+    G = [wl.normal((M, r, c), stream=34, block=i) for i, (r, c) in enumerate(shapes)]
+    V0 = [wl.start_vectors(M, c, block=i, stream=34) for i, (r, c) in enumerate(shapes)]
+    w = [dev(a) for a in W0]
+    mom = [torch.zeros((M, r, c), device="cuda") for r, c in shapes]
+    grad = [dev(a) for a in G]
+    u_out = [torch.zeros((M, r, c), dtype=torch.bfloat16, device="cuda") for r, c in shapes]
+    d_out = [torch.zeros((r, c), dtype=torch.bfloat16, device="cuda") for r, c in shapes]
+    plan = P.StepPlan(w, mom, grad, beta=0.9, lr=lr, ns_steps=3, power_iters=2, v0=[dev(a) for a in V0],
+                      update_rsqrt_mn="op_norm", u_out=u_out, d_out=d_out)
+    P.signmuon_step(ctx, plan)
+    torch.cuda.synchronize()
+    for i, (r, c) in enumerate(shapes):
+        U = u_out[i].float().cpu().numpy()
+        signs = np.stack([O.pack_bits(O.sign_entries(U[p])) for p in range(M)])
+        vote, _ = O.majority_vote_bits(signs, M, r * c)
+        S = vote.reshape(r, c).astype(np.float32)
+        assert np.array_equal(d_out[i].float().cpu().numpy(), S)
+        moved = (W0[i].astype(np.float64) - w[i].cpu().numpy().astype(np.float64)) * S      # = step, entry by entry
+        step_ref = lr / float(O.power_iter(S, 2, 1e-12, V0[i][0]))
+        assert abs(moved.mean() - step_ref) <= 1e-3 * step_ref, (i, moved.mean(), step_ref)
+        assert np.all(np.abs(moved - moved.mean()) <= 2e-3 * step_ref)                      # one step size per block
+    with pytest.raises(P.SignMuonError):                                                    # not with a local polar step
+        P.signmuon_step(ctx, P.StepPlan(w, mom, grad, beta=0.9, lr=lr, ns_steps=3, v0=[dev(a) for a in V0],
+                                        update_rsqrt_mn="op_norm", local_polar_steps=2))
+
+
 def test_step_spectral(P, ctx):
     run_step_case(P, ctx, [(128, 256), (256, 128)], 2, sign_fmt="1bit", Kp=2, scale="spectral")
 
