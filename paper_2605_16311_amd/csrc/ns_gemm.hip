@@ -1,19 +1,22 @@
 // Newton-Schulz GEMMs of Alg. PolarNS on the gfx950 matrix cores: pipelined kernel, K slices of 64.
 //
-//   C = alpha * scale^pow * (opA * opB^T) + gamma * R + diag * I      (bf16 in, fp32 accumulate)
+//   C = rnd(rnd(alpha * scale^pow * (A' * B'^T) + diag * I) + gamma * R),
+//       A' = opA + a_diag I,  B' = opB + b_diag I         (16-bit operands, fp32 accumulate)
 //
 // opA is an M x K operand and opB an N x K operand; each may be stored K-contiguous
-// ([rows][K], "KC") or MN-contiguous ([K][rows], "MN").  The four half-steps of the iteration are
-//   Gram,  rows <= cols : A = B = Y           (KC, KC)   symmetric output
-//   Gram,  rows >  cols : A = B = Y           (MN, MN)   symmetric output
-//   apply, rows <= cols : A = Bm, B = Y       (KC, MN)   Y' = Bm Y
-//   apply, rows >  cols : A = Y,  B = Bm      (KC, KC)   Y' = Y Bm   (Bm symmetric)
+// ([rows][K], "KC") or MN-contiguous ([K][rows], "MN").  The products of the iteration are
+//   Gram of Y,  rows <= cols : A = B = Y           (KC, KC)   symmetric output, bf16 in
+//   Gram of Y,  rows >  cols : A = B = Y           (MN, MN)   symmetric output, bf16 in
+//   s x s products           : A = A_k (+ shift), B = A_k | T | P   (KC, KC), symmetric, half precision
+//   apply,      rows <= cols : A = S, B = Y        (KC, MN)   Y' = S Y      (S = Bm or P_K), bf16
+//   apply,      rows >  cols : A = Y, B = S        (KC, KC)   Y' = Y S      (S symmetric), bf16
 // so Y is only ever read in its own row-major layout and no transposed copy exists.  The
-// layout is a per-problem flag: one launch covers every matrix of a half-step.
+// layout is a per-problem flag: one launch covers every matrix of a phase.  The apply can emit
+// the packed signs of its result (Alg. 3's encoding) besides or instead of the result itself.
 //
 // Structure.  A workgroup of 8 waves (2 per SIMD) owns a TS x TS tile of C (TS = 256, or 128
 // for launches with little work); each wave a (TS/2) x (TS/4) sub-tile held as accumulators of
-// v_mfma_f32_32x32x16_bf16.  K advances in slices of 64 (four MFMA k-steps), so that every
+// v_mfma_f32_32x32x16_bf16 (or _f16).  K advances in slices of 64 (four MFMA k-steps), so that every
 // global->LDS request covers a whole 128-byte line of a K-contiguous operand: the per-CU
 // L2 -> LDS path is limited by the number of outstanding requests, not by bytes.
 // Two LDS stages.  Timeline of slice j (stage j & 1):
@@ -39,7 +42,7 @@
 // belongs in its slot.
 //
 // Symmetric outputs: only tiles with tile_m <= tile_n are computed; off-diagonal tiles are
-// also stored mirrored.
+// also stored mirrored (from the same staged copy, with transposing LDS reads).
 #include "common.h"
 
 namespace sm_gemm {

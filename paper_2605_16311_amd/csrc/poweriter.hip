@@ -14,9 +14,7 @@ constexpr int TPB = 256;
 
 struct pi_args {
   int n;
-  int P_unused;
   float eps;
-  int pad_;
   sm_pi_desc d[SM_PI_MAX_GROUP];
 };
 
@@ -166,9 +164,7 @@ int sm_launch_power_iter_group(signmuon_ctx* ctx, const sm_pi_desc* descs, int n
     long long b_xv = 0, b_xtu = 0, b_nrm = 0;
     for (pi_args* a : {&a_xv, &a_xtu, &a_nrm}) {
       a->n = g;
-      a->P_unused = 0;
       a->eps = eps;
-      a->pad_ = 0;
     }
     for (int i = 0; i < g; ++i) {
       const sm_pi_desc& d = descs[done + i];
