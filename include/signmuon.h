@@ -99,8 +99,11 @@ int signmuon_momentum(signmuon_ctx* ctx, float* mom, const float* grad, const fl
  *   Y0 = X / max(sigma, eps);  `steps` times  Y <- Y (a I + b A + c A^2), A = Y^T Y,
  * evaluated through the Gram matrix of the short side (Y Y^T when rows < cols;
  * the same polynomial of the singular values).  coeffs = {a, b, c} (HOST array);
- * the paper's iteration is {1.5, -0.5, 0}.  Arithmetic: bf16 operands, fp32
- * accumulation on the matrix cores, whatever the storage type of x.
+ * the paper's iteration is {1.5, -0.5, 0}.  Arithmetic: Y in bf16 with fp32
+ * accumulation on the matrix cores, whatever the storage type of x.  For the cubic
+ * with |a| <= 1.5 the steps are regrouped in segments of at most 5: one Gram of Y,
+ * products of s x s matrices (s = the short side; kept in IEEE half precision), one
+ * apply to Y -- the same iteration up to rounding order.
  *   v0 [batch][cols] f32: PowerIter start vector per matrix; required iff
  *   scale == SM_SCALE_SPECTRAL (the paper's random sample, made an input). */
 int signmuon_polar_ns(signmuon_ctx* ctx, void* x, int dtype, int batch, int rows, int cols,
