@@ -565,6 +565,26 @@ static int fill_tiles(sm_gemm_args& args, bool sym, int ts) {
 }  // namespace sm_gemm
 using namespace sm_gemm;
 
+// Host-side check hook: the tile bookkeeping of a launch, without launching.  Fills xcd_begin[9] and
+// tile_begin[n_prob]; returns the total number of tiles, or -1 on bad arguments.
+extern "C" int signmuon_debug_tile_ranges(int n_prob, const int* M, const int* N, const int* K, const int* batch,
+                                          const int* mate, int sym, int ts, int* xcd_begin, int* tile_begin) {
+  if (n_prob < 1 || n_prob > SM_GEMM_MAX_PROB || (ts != 128 && ts != 256)) return -1;
+  sm_gemm_args a;
+  a.n_prob = n_prob;
+  for (int i = 0; i < n_prob; ++i) {
+    a.p[i].M = M[i];
+    a.p[i].N = N[i];
+    a.p[i].K = K[i];
+    a.p[i].batch = batch[i];
+    a.p[i].mate = mate ? mate[i] : 0;
+  }
+  fill_tiles(a, sym != 0, ts);
+  for (int x = 0; x < 9; ++x) xcd_begin[x] = a.xcd_begin[x];
+  for (int i = 0; i < n_prob; ++i) tile_begin[i] = a.p[i].tile_begin;
+  return a.total_tiles;
+}
+
 // Per problem, P.layout bit 0: A is MN-contiguous, bit 1: B is MN-contiguous.  sym: symmetric
 // output, layout 0 or 3 (A and B may differ as long as the product is symmetric).  Otherwise
 // layout 0 or 2.  K multiple of 64.

@@ -59,3 +59,44 @@ def test_product_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in src, f
+
+
+def _tile_ranges(lib, probs, sym, ts):
+    import ctypes as C
+    n = len(probs)
+    arr = lambda vals: (C.c_int * n)(*vals)
+    xcd = (C.c_int * 9)()
+    begin = (C.c_int * n)()
+    total = lib.signmuon_debug_tile_ranges(n, arr([p[0] for p in probs]), arr([p[1] for p in probs]),
+                                           arr([p[2] for p in probs]), arr([p[3] for p in probs]),
+                                           arr([p[4] for p in probs]), int(sym), ts, xcd, begin)
+    return total, list(xcd), list(begin)
+
+
+def test_gemm_tile_ranges_cover_the_list_and_balance_cost():
+    """Host logic of the grouped GEMM launch: the tile list of a launch is cut into eight contiguous
+    ranges (one per XCD) of nearly equal estimated cost; a problem with a mate owns both problems' tiles."""
+    import ctypes as C
+    import torch  # noqa: F401  (loads the HIP runtime the library links against)
+    lib = C.CDLL(LIB)
+    lib.signmuon_debug_tile_ranges.restype = C.c_int
+    # the four nanoGPT classes of a symmetric Gram launch: (M, N, K, batch, mate)
+    probs = [(768, 768, 2304, 96, 0), (768, 768, 768, 96, 0), (768, 768, 3072, 96, 0), (768, 768, 3072, 96, 0)]
+    total, xcd, begin = _tile_ranges(lib, probs, True, 256)
+    assert total == 4 * 96 * 6 and begin == [0, 576, 1152, 1728]
+    assert xcd[0] == 0 and xcd[8] == total and all(a <= b for a, b in zip(xcd, xcd[1:]))
+    cost = []
+    for x in range(8):
+        c = 0.0
+        for t in range(xcd[x], xcd[x + 1]):
+            k = probs[max(i for i in range(4) if begin[i] <= t)][2]
+            c += k / 64 + 6.0
+        cost.append(c)
+    assert max(cost) <= 1.02 * (sum(cost) / 8) + 60.0          # within a tile of the mean
+    # equal problems, no symmetry, small tile: equal counts
+    total, xcd, _ = _tile_ranges(lib, [(256, 512, 256, 8, 0)], False, 128)
+    assert total == 2 * 4 * 8 and [b - a for a, b in zip(xcd, xcd[1:])] == [8] * 8
+    # a leader with a mate owns the tiles of both; the mate's range is empty and sits at the leader's end
+    total, xcd, begin = _tile_ranges(lib, [(768, 768, 768, 10, 1), (768, 768, 768, 10, 0), (512, 512, 512, 3, 0)], True, 256)
+    assert begin == [0, 120, 120] and total == 120 + 3 * 3
+    assert lib.signmuon_debug_tile_ranges(0, None, None, None, None, None, 1, 256, None, None) == -1
