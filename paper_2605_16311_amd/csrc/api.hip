@@ -320,7 +320,7 @@ int run_ns_stepwise(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const f
 // over its short side and Q_k = a I + b A_k, every Y_k is Y_0 times a polynomial in A_0, so
 // all of these commute and
 //     A_{k+1} = Q_k A_k Q_k,      Y_K = (Q_{K-1} ... Q_1 Q_0) Y_0
-// hold exactly: K steps of Alg. PolarNS cost one Gram of Y, 3 (K - 1) products of s x s
+// hold exactly: K steps of Alg. PolarNS cost one Gram of Y, a chain of products of s x s
 // matrices and one apply to Y, and Y is rounded to bf16 once instead of K times.  The s x s
 // matrices are kept in IEEE half precision (all of their entries are bounded by a^K, and the
 // half-precision MFMA runs at the bf16 rate): with three more mantissa bits than bf16 their
@@ -330,6 +330,9 @@ int run_ns_stepwise(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const f
 // Rounding can leave A_k with small negative eigenvalues, which the recurrence grows by
 // a^2 per step (the step-by-step form cannot have them), so a segment covers at most
 // SM_NS_SEGMENT steps and longer iterations re-form the Gram matrix from Y between segments.
+// Segments of three or more steps advance two steps at a time (see below: 5, 7, 10 products
+// for 3, 4, 5 steps); a segment of two, or pairs == false, advances one step at a time with
+// three products per step:
 //   Gram     : A_0 = inv^2 Y Y^T
 //   L1(k)    : T = Q_k A_k   and   P_{k+1} = Q_k P_k   (P_2 = Q_1 Q_0 from A_1 and A_0)
 //   L2(k)    : A_{k+1} = Q_k T
@@ -337,7 +340,7 @@ int run_ns_stepwise(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const f
 constexpr int SM_NS_SEGMENT = 5;
 
 int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coeffs, bool use_scale,
-                      int* cur_io, const ns_sign_req* signs) {
+                      int* cur_io, const ns_sign_req* signs, bool pairs) {
   int cur = *cur_io;
   const float a = coeffs[0], b = coeffs[1];
   if (b == 0.f) return SM_EINVAL;  // run_ns routes b == 0 to the step-by-step form
@@ -371,49 +374,126 @@ int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const
     gemm_params qq = qx;
     qq.alpha = b * b;
     qq.b_diag = a / b;
-    for (int k = 0; k + 1 < kk; ++k) {
-      // A_k: k == 0 in off_q[0], afterwards a_ptr(ai)
-      auto ak = [&](ns_class& cl) { return k == 0 ? at<bf16_t>(ctx, cl.off_q[0]) : a_ptr(cl, ai); };
-      const bool with_p = (k >= 2);
-      rc = launch_over_classes(ctx, pl, qx, with_p ? 2 : 1, [&](ns_class& cl, sm_gemm_prob* P) {
-        small_product(cl, P[0], ak(cl), ak(cl), at<bf16_t>(ctx, cl.off_t), cl.count * mult);
-        if (with_p)
-          small_product(cl, P[1], ak(cl), at<bf16_t>(ctx, cl.off_p[pi]), at<bf16_t>(ctx, cl.off_p[pi ^ 1]),
-                        cl.count * mult);
-      });
-      if (rc != SM_OK) return rc;
-      if (with_p) pi ^= 1;
-      if (k == 1) {  // P_2 from A_1 and A_0
-        rc = launch_over_classes(ctx, pl, qq, 1, [&](ns_class& cl, sm_gemm_prob* P) {
-          small_product(cl, P[0], ak(cl), at<bf16_t>(ctx, cl.off_q[0]), at<bf16_t>(ctx, cl.off_p[pi]), cl.count * mult);
+    int p_final = -1;  // -1: P_1 = Q_0 (bf16, in off_q[0]); else index into off_p
+    if (pairs && kk >= 3) {
+      // Two steps at a time.  With x an eigenvalue of A_k, Q_{k+1} Q_k is the quartic
+      //   q(x) = (a + b x)(a + b x (a + b x)^2) = b^4 E (E + u) + g x + a^2,
+      //   E = x (x + h),  h = 3a / 2b,  u = 3a^2 / 4b^2,  g = a b - a^3 b / 8,
+      // so q(A_k) takes two products (E, then q with A_k as the added term) and
+      // A_{k+2} = q^2 A_k two more: four or five products per two steps instead of six, two of
+      // them squares (one operand matrix to read).
+      //   pair:   E = A (A + h I);  q = b^4 E (E + u I) + g A + a^2 I;
+      //           S = q q  and  P' = q P  (the first pair's q is P_2 itself);  A' = S A
+      //   single: P' = Q P  (an odd step count ends with one ordinary step)
+      // A_k alternates between off_q[0] and off_a, E and S share off_t, q of a later pair sits in off_q[1].
+      const float h = 1.5f * a / b, u = 0.75f * a * a / (b * b);
+      gemm_params pe;  // E
+      pe.in_f16 = pe.out_f16 = true;
+      pe.b_diag = h;
+      gemm_params pq = pe;  // q
+      pq.alpha = b * b * b * b;
+      pq.b_diag = u;
+      pq.diag = a * a;
+      pq.gamma = a * b - a * a * a * b / 8.f;
+      pq.r_f16 = true;
+      gemm_params pm;  // plain product of stored matrices
+      pm.in_f16 = pm.out_f16 = true;
+      auto ab = [&](ns_class& cl, int which) { return at<bf16_t>(ctx, which == 0 ? cl.off_q[0] : cl.off_a); };
+      int left = kk, aw = 0, pw = -1;  // steps to go; where A_k is; which off_p holds P (-1: none yet)
+      while (left >= 2) {
+        const bool first = (pw < 0), fin = (left == 2);
+        rc = launch_over_classes(ctx, pl, pe, 1, [&](ns_class& cl, sm_gemm_prob* P) {
+          small_product(cl, P[0], ab(cl, aw), ab(cl, aw), at<bf16_t>(ctx, cl.off_t), cl.count * mult);
         });
         if (rc != SM_OK) return rc;
+        auto qb = [&](ns_class& cl) { return at<bf16_t>(ctx, first ? cl.off_p[0] : cl.off_q[1]); };
+        rc = launch_over_classes(ctx, pl, pq, 1, [&](ns_class& cl, sm_gemm_prob* P) {
+          const bf16_t* e = at<bf16_t>(ctx, cl.off_t);
+          small_product(cl, P[0], e, e, qb(cl), cl.count * mult);
+          P[0].R = ab(cl, aw);
+        });
+        if (rc != SM_OK) return rc;
+        if (!fin) {
+          rc = launch_over_classes(ctx, pl, pm, first ? 1 : 2, [&](ns_class& cl, sm_gemm_prob* P) {
+            small_product(cl, P[0], qb(cl), qb(cl), at<bf16_t>(ctx, cl.off_t), cl.count * mult);
+            if (!first)
+              small_product(cl, P[1], qb(cl), at<bf16_t>(ctx, cl.off_p[pw]), at<bf16_t>(ctx, cl.off_p[pw ^ 1]),
+                            cl.count * mult);
+          });
+          if (rc != SM_OK) return rc;
+          rc = launch_over_classes(ctx, pl, pm, 1, [&](ns_class& cl, sm_gemm_prob* P) {
+            small_product(cl, P[0], at<bf16_t>(ctx, cl.off_t), ab(cl, aw), ab(cl, aw ^ 1), cl.count * mult);
+          });
+          if (rc != SM_OK) return rc;
+          aw ^= 1;
+          pw = first ? 0 : (pw ^ 1);
+        } else {  // kk == 4: P_4 = q_2 P_2, in bf16 for the apply
+          gemm_params lp = pm;
+          lp.out_f16 = false;
+          rc = launch_over_classes(ctx, pl, lp, 1, [&](ns_class& cl, sm_gemm_prob* P) {
+            small_product(cl, P[0], qb(cl), at<bf16_t>(ctx, cl.off_p[pw]), at<bf16_t>(ctx, cl.off_p[pw ^ 1]),
+                          cl.count * mult);
+          });
+          if (rc != SM_OK) return rc;
+          pw ^= 1;
+        }
+        left -= 2;
       }
-      const int an = (k == 0) ? 0 : (ai ^ 1);
-      rc = launch_over_classes(ctx, pl, qx, 1, [&](ns_class& cl, sm_gemm_prob* P) {
-        small_product(cl, P[0], ak(cl), at<bf16_t>(ctx, cl.off_t), a_ptr(cl, an), cl.count * mult);
-      });
-      if (rc != SM_OK) return rc;
-      ai = an;
-    }
-    int p_final = -1;  // -1: P_1 = Q_0 (bf16, in off_q[0]); else index into off_p
-    if (kk == 2) {  // P_2 = Q_1 Q_0, written in bf16 for the apply
-      gemm_params lp = qq;
-      lp.out_f16 = false;
-      rc = launch_over_classes(ctx, pl, lp, 1, [&](ns_class& cl, sm_gemm_prob* P) {
-        small_product(cl, P[0], a_ptr(cl, ai), at<bf16_t>(ctx, cl.off_q[0]), at<bf16_t>(ctx, cl.off_p[0]), cl.count * mult);
-      });
-      if (rc != SM_OK) return rc;
-      p_final = 0;
-    } else if (kk > 2) {  // P_K = Q_{kk-1} P_{kk-1}
-      gemm_params lp = qx;
-      lp.out_f16 = false;
-      rc = launch_over_classes(ctx, pl, lp, 1, [&](ns_class& cl, sm_gemm_prob* P) {
-        small_product(cl, P[0], a_ptr(cl, ai), at<bf16_t>(ctx, cl.off_p[pi]), at<bf16_t>(ctx, cl.off_p[pi ^ 1]),
-                      cl.count * mult);
-      });
-      if (rc != SM_OK) return rc;
-      p_final = pi ^ 1;
+      if (left == 1) {  // P_K = Q_{K-1} P_{K-1}, in bf16 for the apply
+        gemm_params lp = qx;
+        lp.out_f16 = false;
+        rc = launch_over_classes(ctx, pl, lp, 1, [&](ns_class& cl, sm_gemm_prob* P) {
+          small_product(cl, P[0], ab(cl, aw), at<bf16_t>(ctx, cl.off_p[pw]), at<bf16_t>(ctx, cl.off_p[pw ^ 1]),
+                        cl.count * mult);
+        });
+        if (rc != SM_OK) return rc;
+        pw ^= 1;
+      }
+      p_final = pw;
+    } else {
+      for (int k = 0; k + 1 < kk; ++k) {
+        // A_k: k == 0 in off_q[0], afterwards a_ptr(ai)
+        auto ak = [&](ns_class& cl) { return k == 0 ? at<bf16_t>(ctx, cl.off_q[0]) : a_ptr(cl, ai); };
+        const bool with_p = (k >= 2);
+        rc = launch_over_classes(ctx, pl, qx, with_p ? 2 : 1, [&](ns_class& cl, sm_gemm_prob* P) {
+          small_product(cl, P[0], ak(cl), ak(cl), at<bf16_t>(ctx, cl.off_t), cl.count * mult);
+          if (with_p)
+            small_product(cl, P[1], ak(cl), at<bf16_t>(ctx, cl.off_p[pi]), at<bf16_t>(ctx, cl.off_p[pi ^ 1]),
+                          cl.count * mult);
+        });
+        if (rc != SM_OK) return rc;
+        if (with_p) pi ^= 1;
+        if (k == 1) {  // P_2 from A_1 and A_0
+          rc = launch_over_classes(ctx, pl, qq, 1, [&](ns_class& cl, sm_gemm_prob* P) {
+            small_product(cl, P[0], ak(cl), at<bf16_t>(ctx, cl.off_q[0]), at<bf16_t>(ctx, cl.off_p[pi]), cl.count * mult);
+          });
+          if (rc != SM_OK) return rc;
+        }
+        const int an = (k == 0) ? 0 : (ai ^ 1);
+        rc = launch_over_classes(ctx, pl, qx, 1, [&](ns_class& cl, sm_gemm_prob* P) {
+          small_product(cl, P[0], ak(cl), at<bf16_t>(ctx, cl.off_t), a_ptr(cl, an), cl.count * mult);
+        });
+        if (rc != SM_OK) return rc;
+        ai = an;
+      }
+        if (kk == 2) {  // P_2 = Q_1 Q_0, written in bf16 for the apply
+        gemm_params lp = qq;
+        lp.out_f16 = false;
+        rc = launch_over_classes(ctx, pl, lp, 1, [&](ns_class& cl, sm_gemm_prob* P) {
+          small_product(cl, P[0], a_ptr(cl, ai), at<bf16_t>(ctx, cl.off_q[0]), at<bf16_t>(ctx, cl.off_p[0]), cl.count * mult);
+        });
+        if (rc != SM_OK) return rc;
+        p_final = 0;
+      } else if (kk > 2) {  // P_K = Q_{kk-1} P_{kk-1}
+        gemm_params lp = qx;
+        lp.out_f16 = false;
+        rc = launch_over_classes(ctx, pl, lp, 1, [&](ns_class& cl, sm_gemm_prob* P) {
+          small_product(cl, P[0], a_ptr(cl, ai), at<bf16_t>(ctx, cl.off_p[pi]), at<bf16_t>(ctx, cl.off_p[pi ^ 1]),
+                        cl.count * mult);
+        });
+        if (rc != SM_OK) return rc;
+        p_final = pi ^ 1;
+      }
     }
     gemm_params ap;
     ap.klass = SM_K_NS_APPLY;
@@ -444,8 +524,12 @@ int run_ns(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coe
     const char* e = getenv("SIGNMUON_NS_PATH");
     return e && strcmp(e, "stepwise") == 0;
   }();
+  static const bool force_single = [] {  // the recurrence one step at a time (3 products per step)
+    const char* e = getenv("SIGNMUON_NS_PATH");
+    return e && strcmp(e, "single") == 0;
+  }();
   if (!force_stepwise && coeffs[2] == 0.f && coeffs[1] != 0.f && fabsf(coeffs[0]) <= 1.5f && steps >= 2)
-    return run_ns_recurrence(ctx, pl, mult, steps, coeffs, use_scale, cur_io, signs);
+    return run_ns_recurrence(ctx, pl, mult, steps, coeffs, use_scale, cur_io, signs, !force_single);
   return run_ns_stepwise(ctx, pl, mult, steps, coeffs, use_scale, cur_io, signs);
 }
 
