@@ -289,6 +289,10 @@ NS_CASES = [
     (2, 256, 640, 10, "fro", O.PAPER_COEFFS),       # two full segments, wide
     (1, 512, 512, 10, "spectral", O.PAPER_COEFFS),  # square, near convergence
     (2, 136, 200, 6, "fro", O.PAPER_COEFFS),        # padding + two segments (5 + 1)
+    (2, 192, 448, 8, "fro", O.PAPER_COEFFS),        # segments 5 + 3: two steps at a time, then one
+    (2, 448, 192, 9, "fro", O.PAPER_COEFFS),        # segments 5 + 4: two pairs, tall
+    (2, 256, 384, 5, "fro", (1.25, -0.4, 0.0)),     # another cubic on the short-side recurrence
+    (2, 256, 384, 4, "none", (1.4, -0.45, 0.0)),
 ]
 
 
