@@ -332,9 +332,8 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
   const bf16_t* __restrict__ R = P.R ? P.R + (long long)b * P.sC : nullptr;
   const bool rf16 = args.r_f16 != 0;
   const float gamma = args.gamma;
-  // 8 staged outputs + gamma R at element offset off, rounded again
-  auto add_r = [&](u32x4 v, const bf16_t* r, long long off) -> u32x4 {
-    const u32x4 a = *reinterpret_cast<const u32x4*>(r + off);
+  // 8 staged outputs + gamma times 8 elements of R, rounded again
+  auto add_r = [&](u32x4 v, u32x4 a) -> u32x4 {
     u32x4 w;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -375,16 +374,27 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
   if (SYM || C) {
     // rows: thread t handles chunk t % CPR of rows t / CPR + RPP * k
     const int rc = etid % CPR, rr = etid / CPR;
+    const int gc = n0 + rc * 8;
+    // with an R term: all of its pieces are requested before the first is used, so the read-out
+    // pays one memory latency, not one per piece
+    u32x4 rv[PASSES];
+    if (R) {
+#pragma unroll
+      for (int k = 0; k < PASSES; ++k) {
+        const int gr = m0 + rr + RPP * k;
+        rv[k] = u32x4{0u, 0u, 0u, 0u};
+        if (gr < M && gc < N) rv[k] = *reinterpret_cast<const u32x4*>(R + (long long)gr * P.ldc + gc);
+      }
+    }
 #pragma unroll
     for (int k = 0; k < PASSES; ++k) {
       const int row = rr + RPP * k;  // tile row; (row >> 6) == (RPP * k) >> 6 is a constant
       const unsigned char* sp = stage((RPP * k) >> 6);
       const u32x4 v = *reinterpret_cast<const u32x4*>(sp + (row & 63) * RB + ((rc ^ (row & (CPR - 1))) << 4));
-      const int gr = m0 + row, gc = n0 + rc * 8;
+      const int gr = m0 + row;
       if (gr < M && gc < N) {
         const long long off = (long long)gr * P.ldc + gc;
-        const u32x4 w = R ? add_r(v, R, off) : v;
-        *reinterpret_cast<u32x4*>(C + off) = w;
+        *reinterpret_cast<u32x4*>(C + off) = R ? add_r(v, rv[k]) : v;
       }
     }
   }
@@ -437,8 +447,19 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
     const int rchunk = G % NRC;
     const unsigned char* sp = stage((8 * (ewv * 4 % NRC)) >> 6);  // (8 * rchunk) >> 6 is wave-uniform
     const int r0 = 8 * rchunk + (i16 >> 2);
+    constexpr int MIT = (TS / 16) / CPI;
+    const int gc = m0 + 8 * rchunk;
+    u32x4 rv[MIT];
+    if (R) {
 #pragma unroll
-    for (int k = 0; k < (TS / 16) / CPI; ++k) {
+      for (int k = 0; k < MIT; ++k) {
+        const int gr = n0 + 16 * (CPI * k + G / NRC) + i16;
+        rv[k] = u32x4{0u, 0u, 0u, 0u};
+        if (gr < N && gc < M) rv[k] = *reinterpret_cast<const u32x4*>(R + (long long)gr * P.ldc + gc);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < MIT; ++k) {
       const int cb = 16 * (CPI * k + G / NRC);
       const int col = cb + 4 * (i16 & 3);
       const unsigned char* p0 = sp + (r0 & 63) * RB + ((((col >> 3) ^ (r0 & (CPR - 1)))) << 4) + (col & 7) * 2;
@@ -446,11 +467,11 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
       const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p0));
       const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p1));
       const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-      const int gr = n0 + cb + i16, gc = m0 + 8 * rchunk;
+      const int gr = n0 + cb + i16;
       if (gr < N && gc < M) {
         const long long off = (long long)gr * P.ldc + gc;
         const u32x4 vv = __builtin_bit_cast(u32x4, v);
-        *reinterpret_cast<u32x4*>(C + off) = R ? add_r(vv, R, off) : vv;
+        *reinterpret_cast<u32x4*>(C + off) = R ? add_r(vv, rv[k]) : vv;
       }
     }
   }
