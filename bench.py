@@ -329,7 +329,10 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "M": main_res["M"], "blocks": main_res["n_blocks"],
                    "entries": main_res["entries"], "ns_steps": main_res["ns_steps"],
-                   "local_polar_steps": main_res["local_polar_steps"], "scale": main_res["scale"]},
+                   "local_polar_steps": main_res["local_polar_steps"], "scale": main_res["scale"],
+                   # Y, Gram and apply in bf16; the s x s matrices of the regrouped iteration in IEEE half
+                   # precision (same MFMA rate); fp32 accumulation, momentum and weights
+                   "ns_arithmetic": "bf16 Y / f16 s x s intermediates / f32 accumulate"},
         "roofline": {"kernel": dom_name, "bound": dom["bound"], "achieved": ach, "peak": peak, "unit": unit,
                      "frac": ach / peak, "traffic": traffic, "avg_launch_ms": dom["avg_launch_ms"],
                      "flop_per_launch": dom["flop_per_launch"], "bytes_per_launch": dom["bytes_per_launch"]},
