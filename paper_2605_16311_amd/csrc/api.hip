@@ -339,6 +339,21 @@ int run_ns_stepwise(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const f
 //   last     : P_K = Q_{K-1} P_{K-1};      apply: Y' = inv P_K Y
 constexpr int SM_NS_SEGMENT = 5;
 
+// Coefficients of the two-steps-at-a-time form: with E = x (x + h),
+//   (a + b x)(a + b x (a + b x)^2) = b4 E (E + u) + g x + a2.
+struct pair_coeffs {
+  float h, u, b4, g, a2;
+};
+pair_coeffs pair_coefficients(float a, float b) {
+  pair_coeffs c;
+  c.h = 1.5f * a / b;
+  c.u = 0.75f * a * a / (b * b);
+  c.b4 = b * b * b * b;
+  c.g = a * b - a * a * a * b / 8.f;
+  c.a2 = a * a;
+  return c;
+}
+
 int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coeffs, bool use_scale,
                       int* cur_io, const ns_sign_req* signs, bool pairs) {
   int cur = *cur_io;
@@ -386,15 +401,15 @@ int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const
       //           S = q q  and  P' = q P  (the first pair's q is P_2 itself);  A' = S A
       //   single: P' = Q P  (an odd step count ends with one ordinary step)
       // A_k alternates between off_q[0] and off_a, E and S share off_t, q of a later pair sits in off_q[1].
-      const float h = 1.5f * a / b, u = 0.75f * a * a / (b * b);
+      const pair_coeffs pc = pair_coefficients(a, b);
       gemm_params pe;  // E
       pe.in_f16 = pe.out_f16 = true;
-      pe.b_diag = h;
+      pe.b_diag = pc.h;
       gemm_params pq = pe;  // q
-      pq.alpha = b * b * b * b;
-      pq.b_diag = u;
-      pq.diag = a * a;
-      pq.gamma = a * b - a * a * a * b / 8.f;
+      pq.alpha = pc.b4;
+      pq.b_diag = pc.u;
+      pq.diag = pc.a2;
+      pq.gamma = pc.g;
       pq.r_f16 = true;
       gemm_params pm;  // plain product of stored matrices
       pm.in_f16 = pm.out_f16 = true;
@@ -948,3 +963,14 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
 }
 
 }  // extern "C"
+
+// Host-side check hook: the five coefficients {h, u, b^4, g, a^2} of the two-steps-at-a-time
+// recurrence for the cubic with coefficients a, b.
+extern "C" void signmuon_debug_pair_coefficients(float a, float b, float* out5) {
+  const pair_coeffs c = pair_coefficients(a, b);
+  out5[0] = c.h;
+  out5[1] = c.u;
+  out5[2] = c.b4;
+  out5[3] = c.g;
+  out5[4] = c.a2;
+}

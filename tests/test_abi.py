@@ -100,3 +100,29 @@ def test_gemm_tile_ranges_cover_the_list_and_balance_cost():
     total, xcd, begin = _tile_ranges(lib, [(768, 768, 768, 10, 1), (768, 768, 768, 10, 0), (512, 512, 512, 3, 0)], True, 256)
     assert begin == [0, 120, 120] and total == 120 + 3 * 3
     assert lib.signmuon_debug_tile_ranges(0, None, None, None, None, None, 1, 256, None, None) == -1
+
+
+def test_two_step_recurrence_coefficients_reproduce_two_newton_schulz_steps():
+    """Host logic of the regrouped Newton-Schulz iteration (Alg. PolarNS with c = 0): on an eigenvalue x of
+    the Gram matrix, two steps multiply Y by Q_1 Q_0 with Q_0 = a + b x and Q_1 = a + b x Q_0^2.  The
+    library forms that quartic as b^4 E (E + u) + g x + a^2 with E = x (x + h); check the five
+    coefficients it uses against the two explicit steps."""
+    import ctypes as C
+    import numpy as np
+    import torch  # noqa: F401  (loads the HIP runtime the library links against)
+    lib = C.CDLL(LIB)
+    lib.signmuon_debug_pair_coefficients.restype = None
+    lib.signmuon_debug_pair_coefficients.argtypes = [C.c_float, C.c_float, C.POINTER(C.c_float)]
+    x = np.linspace(0.0, 1.6, 161)
+    for a, b in [(1.5, -0.5), (1.25, -0.4), (1.4, -0.45), (1.0, -0.3), (1.5, 0.25)]:
+        out = (C.c_float * 5)()
+        lib.signmuon_debug_pair_coefficients(a, b, out)
+        h, u, b4, g, a2 = [float(v) for v in out]
+        q0 = a + b * x
+        q1 = a + b * (x * q0 * q0)
+        e = x * (x + h)
+        got = b4 * e * (e + u) + g * x + a2
+        assert np.allclose(got, q1 * q0, rtol=0, atol=2e-5 * max(1.0, np.abs(q1 * q0).max())), (a, b)
+    # the paper's coefficients give exactly representable values
+    lib.signmuon_debug_pair_coefficients(1.5, -0.5, out)
+    assert [float(v) for v in out] == [-4.5, 6.75, 0.0625, -0.5390625, 2.25]
