@@ -420,6 +420,11 @@ struct upd_args {
   sm_upd_desc d[SM_UPD_MAX_GROUP];
 };
 
+// A workgroup owns UPD_ITERS * TPB * 4 consecutive entries of one block: UPD_ITERS rounds of 4 entries per
+// thread, all loads of a round set issued before the first store.
+constexpr int UPD_ITERS = 4;
+constexpr int UPD_CHUNK = UPD_ITERS * TPB * 4;
+
 __global__ void __launch_bounds__(TPB) sm_update_kernel(const upd_args g) {
   int di = 0;
   while (di + 1 < g.n && (int)blockIdx.x >= g.d[di + 1].block_begin) ++di;
@@ -429,22 +434,46 @@ __global__ void __launch_bounds__(TPB) sm_update_kernel(const upd_args g) {
   const int cols = D.cols, ld = D.ld;
   const float step = D.kappa ? __fmul_rn(D.step, D.kappa[0]) : D.step;
   const long long n = (long long)D.rows * cols;
-  const long long e0 = ((long long)(blockIdx.x - D.block_begin) * TPB + threadIdx.x) * 4;
-  if (e0 >= n) return;
-  if (e0 + 4 <= n && (cols & 3) == 0) {
-    const long long di = (ld == cols) ? e0 : (e0 / cols) * ld + (e0 % cols);
-    const bf16x4 h = *reinterpret_cast<const bf16x4*>(d + di);
-    float4 wv = *reinterpret_cast<float4*>(w + e0);
-    wv.x = __fsub_rn(wv.x, __fmul_rn(step, (float)h[0]));
-    wv.y = __fsub_rn(wv.y, __fmul_rn(step, (float)h[1]));
-    wv.z = __fsub_rn(wv.z, __fmul_rn(step, (float)h[2]));
-    wv.w = __fsub_rn(wv.w, __fmul_rn(step, (float)h[3]));
-    *reinterpret_cast<float4*>(w + e0) = wv;
-  } else {
-    for (int k = 0; k < 4 && e0 + k < n; ++k) {
-      const long long e = e0 + k;
-      const float dv = (float)d[(e / cols) * ld + (e % cols)];
-      w[e] = __fsub_rn(w[e], __fmul_rn(step, dv));
+  const long long base = (long long)(blockIdx.x - D.block_begin) * UPD_CHUNK + threadIdx.x * 4;
+  if ((cols & 3) == 0 && base - threadIdx.x * 4 + UPD_CHUNK <= n) {  // a full chunk of whole groups of 4
+    bf16x4 h[UPD_ITERS];
+    float4 wv[UPD_ITERS];
+#pragma unroll
+    for (int it = 0; it < UPD_ITERS; ++it) {
+      const long long e0 = base + (long long)it * (TPB * 4);
+      const long long di4 = (ld == cols) ? e0 : (e0 / cols) * ld + (e0 % cols);
+      h[it] = *reinterpret_cast<const bf16x4*>(d + di4);
+      wv[it] = *reinterpret_cast<const float4*>(w + e0);
+    }
+#pragma unroll
+    for (int it = 0; it < UPD_ITERS; ++it) {
+      const long long e0 = base + (long long)it * (TPB * 4);
+      wv[it].x = __fsub_rn(wv[it].x, __fmul_rn(step, (float)h[it][0]));
+      wv[it].y = __fsub_rn(wv[it].y, __fmul_rn(step, (float)h[it][1]));
+      wv[it].z = __fsub_rn(wv[it].z, __fmul_rn(step, (float)h[it][2]));
+      wv[it].w = __fsub_rn(wv[it].w, __fmul_rn(step, (float)h[it][3]));
+      *reinterpret_cast<float4*>(w + e0) = wv[it];
+    }
+    return;
+  }
+  for (int it = 0; it < UPD_ITERS; ++it) {
+    const long long e0 = base + (long long)it * (TPB * 4);
+    if (e0 >= n) return;
+    if (e0 + 4 <= n && (cols & 3) == 0) {
+      const long long di4 = (ld == cols) ? e0 : (e0 / cols) * ld + (e0 % cols);
+      const bf16x4 h = *reinterpret_cast<const bf16x4*>(d + di4);
+      float4 wv = *reinterpret_cast<float4*>(w + e0);
+      wv.x = __fsub_rn(wv.x, __fmul_rn(step, (float)h[0]));
+      wv.y = __fsub_rn(wv.y, __fmul_rn(step, (float)h[1]));
+      wv.z = __fsub_rn(wv.z, __fmul_rn(step, (float)h[2]));
+      wv.w = __fsub_rn(wv.w, __fmul_rn(step, (float)h[3]));
+      *reinterpret_cast<float4*>(w + e0) = wv;
+    } else {
+      for (int k = 0; k < 4 && e0 + k < n; ++k) {
+        const long long e = e0 + k;
+        const float dv = (float)d[(e / cols) * ld + (e % cols)];
+        w[e] = __fsub_rn(w[e], __fmul_rn(step, dv));
+      }
     }
   }
 }
@@ -840,7 +869,7 @@ int sm_launch_update_group(signmuon_ctx* ctx, const sm_upd_desc* descs, int n) {
     for (int i = 0; i < g; ++i) {
       a.d[i] = descs[done + i];
       a.d[i].block_begin = (int)blocks;
-      blocks += ((((long long)a.d[i].rows * a.d[i].cols + 3) / 4) + TPB - 1) / TPB;
+      blocks += ((long long)a.d[i].rows * a.d[i].cols + UPD_CHUNK - 1) / UPD_CHUNK;
     }
     if (blocks > 0) {
       sm_launch_scope sc(ctx, SM_K_UPDATE);
