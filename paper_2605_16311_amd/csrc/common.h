@@ -82,7 +82,8 @@ struct sm_mom_desc {
   int block_begin;     // first workgroup of this block in the grouped launch
 };
 constexpr int SM_MOM_MAX_GROUP = 40;
-constexpr int SM_MOM_CHUNK = 8192;  // elements per workgroup
+constexpr int SM_MOM_CHUNK = 1024;  // elements per workgroup: one 16-byte piece per thread (short-lived workgroups
+                                    // keep the four streams of the momentum update close together in memory)
 
 int sm_launch_momentum(signmuon_ctx* ctx, const sm_mom_desc* descs, int n, int M, float beta, float wd);
 // sumsq[i] = sum_j partial[i*chunks + j], i < count (fixed order)

@@ -32,10 +32,13 @@ __device__ __forceinline__ unsigned ge0_f32(unsigned u) { return (u <= 0x7F80000
 __device__ __forceinline__ unsigned ge0_bf16(unsigned h) { return (h <= 0x7F80u) | (h == 0x8000u); }
 
 // ------------------------------------------------------------------ momentum
+// start[k]: the block that holds workgroup (k << shift) of the launch, so that a workgroup finds its
+// block in a step or two instead of walking the table (workgroups are short: the walk would show).
 struct mom_args {
   int n, M;
   float beta, omb, wd;
-  int pad_;
+  int shift;
+  int start[64];
   sm_mom_desc d[SM_MOM_MAX_GROUP];
 };
 
@@ -47,7 +50,7 @@ __device__ __forceinline__ float mom_one(float m, float g, float w, const mom_ar
 template <bool VEC>
 __global__ void __launch_bounds__(TPB) sm_momentum_kernel(const mom_args a) {
   __shared__ float red[4];
-  int bi = 0;
+  int bi = a.start[blockIdx.x >> a.shift];
   while (bi + 1 < a.n && (int)blockIdx.x >= a.d[bi + 1].block_begin) ++bi;
   const sm_mom_desc& D = a.d[bi];
   const int local = blockIdx.x - D.block_begin;
@@ -74,13 +77,14 @@ __global__ void __launch_bounds__(TPB) sm_momentum_kernel(const mom_args a) {
       m.y = mom_one(m.y, g.y, ww.y, a, has_wd);
       m.z = mom_one(m.z, g.z, ww.z, a, has_wd);
       m.w = mom_one(m.w, g.w, ww.w, a, has_wd);
-      *reinterpret_cast<f32x4*>(mom + i) = m;
+      // neither the momentum nor its bf16 copy is read again before it has left the caches
+      __builtin_nontemporal_store(m, reinterpret_cast<f32x4*>(mom + i));
       ss += (m.x * m.x + m.y * m.y) + (m.z * m.z + m.w * m.w);
       if (x) {
         if (flat || (D.cols & 3) == 0) {
           const long long xi = flat ? i : (i / D.cols) * D.ld + (i % D.cols);
           bf16x4 h = {(bf16_t)m.x, (bf16_t)m.y, (bf16_t)m.z, (bf16_t)m.w};
-          *reinterpret_cast<bf16x4*>(x + xi) = h;
+          __builtin_nontemporal_store(h, reinterpret_cast<bf16x4*>(x + xi));
         } else {
           const float mv[4] = {m.x, m.y, m.z, m.w};
           for (int k = 0; k < 4; ++k) {
@@ -491,23 +495,29 @@ int sm_launch_momentum(signmuon_ctx* ctx, const sm_mom_desc* descs, int n, int M
     a.beta = beta;
     a.omb = 1.0f - beta;
     a.wd = wd;
-    a.pad_ = 0;
-    int blocks = 0;
+    long long blocks = 0;
     bool vec = true;
     for (int i = 0; i < g; ++i) {
       a.d[i] = descs[done + i];
-      a.d[i].block_begin = blocks;
-      blocks += M * a.d[i].chunks;
+      a.d[i].block_begin = (int)blocks;
+      blocks += (long long)M * a.d[i].chunks;
       const sm_mom_desc& D = a.d[i];
       vec = vec && (D.d % 4 == 0) && sm_aligned(D.mom, 16) && sm_aligned(D.grad, 16) &&
             (!D.w || sm_aligned(D.w, 16)) && (!D.x || (sm_aligned(D.x, 8) && D.ld % 4 == 0 && D.x_stride % 4 == 0));
     }
-    {
+    if (blocks > 0x7FFFFFFFLL) return sm_fail(ctx, SM_EUNSUPPORTED, "momentum: too many entries for one launch");
+    a.shift = 0;
+    while ((blocks >> a.shift) >= 64) ++a.shift;
+    for (int k = 0, bi = 0; k < 64; ++k) {
+      while (bi + 1 < g && ((long long)k << a.shift) >= a.d[bi + 1].block_begin) ++bi;
+      a.start[k] = bi;
+    }
+    if (blocks > 0) {
       sm_launch_scope sc(ctx, SM_K_MOMENTUM);
       if (vec)
-        hipLaunchKernelGGL(sm_momentum_kernel<true>, dim3(blocks), dim3(TPB), 0, ctx->stream, a);
+        hipLaunchKernelGGL(sm_momentum_kernel<true>, dim3((unsigned)blocks), dim3(TPB), 0, ctx->stream, a);
       else
-        hipLaunchKernelGGL(sm_momentum_kernel<false>, dim3(blocks), dim3(TPB), 0, ctx->stream, a);
+        hipLaunchKernelGGL(sm_momentum_kernel<false>, dim3((unsigned)blocks), dim3(TPB), 0, ctx->stream, a);
     }
     SM_HIP(ctx, hipGetLastError());
     done += g;
