@@ -229,6 +229,71 @@ __global__ void __launch_bounds__(TPB) sm_sign_pack_kernel(const sp_args a) {
   }
 }
 
+// 1-bit output when every matrix of the launch can be read in whole 8-entry groups and its output is
+// 4-byte aligned: SPB_UNROLL bytes per thread, all loads issued before the first use, and the
+// bytes of four neighbouring lanes leave as one 32-bit store (byte stores cost a full store slot each).
+constexpr int SPB_UNROLL = 2;
+
+template <int DT>
+__global__ void __launch_bounds__(TPB) sm_sign_pack_bits_kernel(const sp_args a) {
+  int di = 0;
+  while (di + 1 < a.n && (int)blockIdx.x >= a.d[di + 1].block_begin) ++di;
+  const sm_sp_desc& D = a.d[di];
+  const int local = blockIdx.x - D.block_begin;
+  const int b = local / D.blocks_per_row, bx = local - b * D.blocks_per_row;
+  const long long n = D.n, bytes_per_row = D.bytes_per_row;  // a multiple of 8: a 4-lane group is in range as a whole
+  const int cols = D.cols, ld = D.ld;
+  const unsigned short* ub = reinterpret_cast<const unsigned short*>(D.u) + (DT == SM_BF16 ? (long long)b * D.batch_stride : 0);
+  const unsigned* uf = reinterpret_cast<const unsigned*>(D.u) + (DT == SM_F32 ? (long long)b * D.batch_stride : 0);
+  unsigned char* o = reinterpret_cast<unsigned char*>(D.out) + (long long)b * D.out_stride;
+  const long long q0 = ((long long)bx * SPB_UNROLL) * TPB + threadIdx.x;
+  u32x4 v0[SPB_UNROLL], v1[SPB_UNROLL];
+#pragma unroll
+  for (int j = 0; j < SPB_UNROLL; ++j) {
+    const long long e0 = (q0 + (long long)j * TPB) * 8;
+    v0[j] = v1[j] = u32x4{0u, 0u, 0u, 0u};
+    if (e0 + 8 <= n) {
+      const long long src = (ld == cols) ? e0 : (e0 / cols) * ld + (e0 % cols);
+      if (DT == SM_BF16) {
+        v0[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ub + src));
+      } else {
+        v0[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(uf + src));
+        v1[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(uf + src + 4));
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < SPB_UNROLL; ++j) {
+    const long long q = q0 + (long long)j * TPB;  // byte index
+    const long long e0 = q * 8;
+    unsigned bits = 0;
+    if (e0 + 8 <= n) {
+      if (DT == SM_BF16) {
+        const unsigned wv[4] = {v0[j].x, v0[j].y, v0[j].z, v0[j].w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          bits |= ge0_bf16(wv[k] & 0xFFFFu) << (2 * k);
+          bits |= ge0_bf16(wv[k] >> 16) << (2 * k + 1);
+        }
+      } else {
+        const unsigned wv[8] = {v0[j].x, v0[j].y, v0[j].z, v0[j].w, v1[j].x, v1[j].y, v1[j].z, v1[j].w};
+#pragma unroll
+        for (int k = 0; k < 8; ++k) bits |= ge0_f32(wv[k]) << k;
+      }
+    } else {  // the group that holds entry n - 1, and the zero padding after it
+      for (int k = 0; k < 8; ++k) {
+        const long long e = e0 + k;
+        if (e >= n) break;
+        const long long src = (ld == cols) ? e : (e / cols) * ld + (e % cols);
+        bits |= ((DT == SM_BF16) ? ge0_bf16(ub[src]) : ge0_f32(uf[src])) << k;
+      }
+    }
+    bits |= __shfl_down(bits, 1, 64) << 8;
+    bits |= __shfl_down(bits, 2, 64) << 16;
+    if ((threadIdx.x & 3) == 0 && q < bytes_per_row) __builtin_nontemporal_store(bits, reinterpret_cast<unsigned*>(o + q));
+  }
+}
+
 // ------------------------------------------------------------------ vote
 // Voted bits only: one thread = one 64-bit word.  Bit-sliced counting: the M
 // words are added into PLANES binary counter planes with ripple carries
@@ -576,13 +641,18 @@ int sm_launch_sign_pack_group(signmuon_ctx* ctx, const sm_sp_desc* descs, int n,
       sm_sp_desc& D = a.d[i];
       D = descs[done + i];
       D.bytes_per_row = (fmt == SM_SIGN_1BIT) ? 8 * ((D.n + 63) / 64) : (D.n + 7) / 8;  // threads per row
-      D.blocks_per_row = (int)((D.bytes_per_row + TPB * 4 - 1) / (TPB * 4));
-      D.block_begin = blocks;
-      blocks += D.blocks_per_row * M;
       // the fast path reads whole 8-entry groups with 16-byte loads
       fast_ok = fast_ok && (D.ld == D.cols || (D.cols % 8 == 0 && D.ld % 8 == 0)) && sm_aligned(D.u, 16) &&
                 (D.batch_stride % 8 == 0) &&
-                (fmt == SM_SIGN_1BIT || (sm_aligned(D.out, 8) && D.out_stride % 8 == 0));
+                (fmt == SM_SIGN_1BIT ? (sm_aligned(D.out, 4) && D.out_stride % 4 == 0)
+                                     : (sm_aligned(D.out, 8) && D.out_stride % 8 == 0));
+    }
+    const int per_block = TPB * ((fmt == SM_SIGN_1BIT && fast_ok) ? SPB_UNROLL : 4);  // output bytes (threads' groups)
+    for (int i = 0; i < g; ++i) {
+      sm_sp_desc& D = a.d[i];
+      D.blocks_per_row = (int)((D.bytes_per_row + per_block - 1) / per_block);
+      D.block_begin = blocks;
+      blocks += D.blocks_per_row * M;
     }
     if (blocks > 0) {
       const dim3 grid(blocks);
@@ -590,13 +660,19 @@ int sm_launch_sign_pack_group(signmuon_ctx* ctx, const sm_sp_desc* descs, int n,
 #define SP_LAUNCH(DT, FMT, FAST) hipLaunchKernelGGL((sm_sign_pack_kernel<DT, FMT, FAST>), grid, dim3(TPB), 0, ctx->stream, a)
       if (dtype == SM_BF16) {
         if (fmt == SM_SIGN_1BIT) {
-          if (fast_ok) SP_LAUNCH(SM_BF16, SM_SIGN_1BIT, true); else SP_LAUNCH(SM_BF16, SM_SIGN_1BIT, false);
+          if (fast_ok)
+            hipLaunchKernelGGL((sm_sign_pack_bits_kernel<SM_BF16>), grid, dim3(TPB), 0, ctx->stream, a);
+          else
+            SP_LAUNCH(SM_BF16, SM_SIGN_1BIT, false);
         } else {
           if (fast_ok) SP_LAUNCH(SM_BF16, SM_SIGN_INT8, true); else SP_LAUNCH(SM_BF16, SM_SIGN_INT8, false);
         }
       } else {
         if (fmt == SM_SIGN_1BIT) {
-          if (fast_ok) SP_LAUNCH(SM_F32, SM_SIGN_1BIT, true); else SP_LAUNCH(SM_F32, SM_SIGN_1BIT, false);
+          if (fast_ok)
+            hipLaunchKernelGGL((sm_sign_pack_bits_kernel<SM_F32>), grid, dim3(TPB), 0, ctx->stream, a);
+          else
+            SP_LAUNCH(SM_F32, SM_SIGN_1BIT, false);
         } else {
           if (fast_ok) SP_LAUNCH(SM_F32, SM_SIGN_INT8, true); else SP_LAUNCH(SM_F32, SM_SIGN_INT8, false);
         }
