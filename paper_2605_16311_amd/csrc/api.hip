@@ -153,6 +153,7 @@ struct gemm_params {
   int scale_pow = 0;
   bool sym = true;
   bool in_f16 = false, out_f16 = false, r_f16 = false;
+  int sym_store = 0;  // bit 0: operands valid in their upper blocks only; bit 1: write the output that way
   int klass = SM_K_NS_SMALL;
 };
 
@@ -168,7 +169,7 @@ int launch_over_classes(signmuon_ctx* ctx, ns_plan* pl, const gemm_params& gp, i
     ga.in_f16 = gp.in_f16;
     ga.out_f16 = gp.out_f16;
     ga.r_f16 = gp.r_f16;
-    ga.pad_ = 0;
+    ga.sym_store = gp.sym_store;
     ga.alpha = gp.alpha;
     ga.gamma = gp.gamma;
     ga.diag = gp.diag;
@@ -359,6 +360,14 @@ int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const
   int cur = *cur_io;
   const float a = coeffs[0], b = coeffs[1];
   if (b == 0.f) return SM_EINVAL;  // run_ns routes b == 0 to the step-by-step form
+  // The s x s matrices between the Gram and the apply are symmetric: only their 256 x 256 blocks on and
+  // above the diagonal are written, and a product reads the other blocks as transposes of those
+  // (a third fewer bytes to and from memory).  SIGNMUON_NS_STORE=full writes and reads whole matrices.
+  static const bool full_store = [] {
+    const char* e = getenv("SIGNMUON_NS_STORE");
+    return e && strcmp(e, "full") == 0;
+  }();
+  const int ss = full_store ? 0 : 3;
   int done = 0;
   while (done < steps) {
     const int kk = std::min(SM_NS_SEGMENT, steps - done);
@@ -385,6 +394,7 @@ int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const
     qx.alpha = b;
     qx.a_diag = a / b;
     qx.in_f16 = qx.out_f16 = true;
+    qx.sym_store = ss;
     // first product of P: P_2 = Q_1 Q_0 = b^2 (A_1 + (a / b) I) (A_0 + (a / b) I)
     gemm_params qq = qx;
     qq.alpha = b * b;
@@ -404,6 +414,7 @@ int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const
       const pair_coeffs pc = pair_coefficients(a, b);
       gemm_params pe;  // E
       pe.in_f16 = pe.out_f16 = true;
+      pe.sym_store = ss;
       pe.b_diag = pc.h;
       gemm_params pq = pe;  // q
       pq.alpha = pc.b4;
@@ -413,6 +424,7 @@ int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const
       pq.r_f16 = true;
       gemm_params pm;  // plain product of stored matrices
       pm.in_f16 = pm.out_f16 = true;
+      pm.sym_store = ss;
       auto ab = [&](ns_class& cl, int which) { return at<bf16_t>(ctx, which == 0 ? cl.off_q[0] : cl.off_a); };
       int left = kk, aw = 0, pw = -1;  // steps to go; where A_k is; which off_p holds P (-1: none yet)
       while (left >= 2) {
@@ -445,6 +457,7 @@ int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const
         } else {  // kk == 4: P_4 = q_2 P_2, in bf16 for the apply
           gemm_params lp = pm;
           lp.out_f16 = false;
+        lp.sym_store = ss & 1;  // the apply reads P_K as a full matrix
           rc = launch_over_classes(ctx, pl, lp, 1, [&](ns_class& cl, sm_gemm_prob* P) {
             small_product(cl, P[0], qb(cl), at<bf16_t>(ctx, cl.off_p[pw]), at<bf16_t>(ctx, cl.off_p[pw ^ 1]),
                           cl.count * mult);
@@ -457,6 +470,7 @@ int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const
       if (left == 1) {  // P_K = Q_{K-1} P_{K-1}, in bf16 for the apply
         gemm_params lp = qx;
         lp.out_f16 = false;
+        lp.sym_store = ss & 1;  // the apply reads P_K as a full matrix
         rc = launch_over_classes(ctx, pl, lp, 1, [&](ns_class& cl, sm_gemm_prob* P) {
           small_product(cl, P[0], ab(cl, aw), at<bf16_t>(ctx, cl.off_p[pw]), at<bf16_t>(ctx, cl.off_p[pw ^ 1]),
                         cl.count * mult);
@@ -494,6 +508,7 @@ int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const
         if (kk == 2) {  // P_2 = Q_1 Q_0, written in bf16 for the apply
         gemm_params lp = qq;
         lp.out_f16 = false;
+        lp.sym_store = ss & 1;  // the apply reads P_K as a full matrix
         rc = launch_over_classes(ctx, pl, lp, 1, [&](ns_class& cl, sm_gemm_prob* P) {
           small_product(cl, P[0], a_ptr(cl, ai), at<bf16_t>(ctx, cl.off_q[0]), at<bf16_t>(ctx, cl.off_p[0]), cl.count * mult);
         });
@@ -502,6 +517,7 @@ int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const
       } else if (kk > 2) {  // P_K = Q_{kk-1} P_{kk-1}
         gemm_params lp = qx;
         lp.out_f16 = false;
+        lp.sym_store = ss & 1;  // the apply reads P_K as a full matrix
         rc = launch_over_classes(ctx, pl, lp, 1, [&](ns_class& cl, sm_gemm_prob* P) {
           small_product(cl, P[0], a_ptr(cl, ai), at<bf16_t>(ctx, cl.off_p[pi]), at<bf16_t>(ctx, cl.off_p[pi ^ 1]),
                         cl.count * mult);

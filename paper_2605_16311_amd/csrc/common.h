@@ -221,7 +221,8 @@ struct sm_gemm_args {
   float alpha, gamma, diag;
   float a_diag, b_diag;  // 0 = none
   int in_f16, out_f16, r_f16;
-  int pad_;
+  int sym_store;     // bit 0: the operands hold valid data only in their 256 x 256 blocks on and above the diagonal
+                     // (symmetric matrices; half precision, M == N == K); bit 1: write the output that way
   sm_gemm_prob p[SM_GEMM_MAX_PROB];
 };
 // One grouped launch over the problem table.  sym: every problem's output is symmetric (M == N;

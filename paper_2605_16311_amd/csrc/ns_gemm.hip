@@ -43,6 +43,11 @@
 //
 // Symmetric outputs: only tiles with tile_m <= tile_n are computed; off-diagonal tiles are
 // also stored mirrored (from the same staged copy, with transposing LDS reads).
+// The s x s products can also keep their matrices in upper-block storage (sym_store): the
+// mirrored store is skipped outside the diagonal 256 x 256 blocks, and a product reads block
+// (r, c), r > c, of an operand as the transpose of block (c, r) -- the K walk then changes the
+// operand form (MN for the transposed blocks, KC for the stored ones) at block boundaries.
+// A third fewer bytes go to and come from memory, which is what bounds those products.
 #include "common.h"
 
 namespace sm_gemm {
@@ -152,7 +157,7 @@ __device__ __forceinline__ unsigned ge0_bf16(unsigned h) {
 
 // One TS x TS tile of one problem.  The four stage arrays are the kernel's own __shared__
 // variables, passed by reference so that every access keeps its identity after inlining.
-template <int TS, bool A_MN, bool B_MN, bool SYM, bool F16>
+template <int TS, bool A_MN, bool B_MN, bool SYM, bool F16, bool SYMSTORE = false>
 __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gemm_prob& P, int b, int tm, int tn,
                                           unsigned char (&sA0)[TS * 128], unsigned char (&sA1)[TS * 128],
                                           unsigned char (&sB0)[TS * 128], unsigned char (&sB1)[TS * 128]) {
@@ -189,16 +194,17 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
     vb[q] = ob.voff[q];
   }
   const int ksa = __builtin_amdgcn_readfirstlane(oa.kstep), ksb = __builtin_amdgcn_readfirstlane(ob.kstep);
-#define ISSUE(sa, sb, slice)                                                                                          \
+#define ISSUE_V(sa, sb, slice, VA, KSA, VB, KSB)                                                                     \
   {                                                                                                                   \
     _Pragma("unroll") for (int q = 0; q < NLOAD; ++q) {                                                               \
-      const int voa = va[q], vob = vb[q];                                                                             \
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, LDS_PTR((sa) + (NLOAD * wv + q) * 1024), 16, voa, (slice) * ksa,   \
+      const int voa = VA[q], vob = VB[q];                                                                             \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, LDS_PTR((sa) + (NLOAD * wv + q) * 1024), 16, voa, (slice) * (KSA), \
                                                0, 0);                                                                 \
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, LDS_PTR((sb) + (NLOAD * wv + q) * 1024), 16, vob, (slice) * ksb,   \
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, LDS_PTR((sb) + (NLOAD * wv + q) * 1024), 16, vob, (slice) * (KSB), \
                                                0, 0);                                                                 \
     }                                                                                                                 \
   }
+#define ISSUE(sa, sb, slice) ISSUE_V(sa, sb, slice, va, ksa, vb, ksb)
 
   f32x16 acc[FM][FN];
 #pragma unroll
@@ -210,11 +216,12 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
 
   // two fragment sets: while the matrix pipe works through one, the LDS reads of the other are in flight
   bf16x8 fa[2][FM], fb[2][FN];
-#define FETCH(set, sa, sb, ks)                                                          \
+#define FETCH_L(set, sa, sb, ks, LA, LB)                                                \
   {                                                                                     \
-    _Pragma("unroll") for (int i = 0; i < FM; ++i) fa[set][i] = oa.fetch(sa, i, ks);    \
-    _Pragma("unroll") for (int j = 0; j < FN; ++j) fb[set][j] = ob.fetch(sb, j, ks);    \
+    _Pragma("unroll") for (int i = 0; i < FM; ++i) fa[set][i] = LA.fetch(sa, i, ks);    \
+    _Pragma("unroll") for (int j = 0; j < FN; ++j) fb[set][j] = LB.fetch(sb, j, ks);    \
   }
+#define FETCH(set, sa, sb, ks) FETCH_L(set, sa, sb, ks, oa, ob)
 #define MMA(set)                                                                                                \
   {                                                                                                             \
     _Pragma("unroll") for (int i = 0; i < FM; ++i) _Pragma("unroll") for (int j = 0; j < FN; ++j) {             \
@@ -285,25 +292,118 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
   }
   const int nk = K / BK;
   int j = 0;
-  ISSUE(sA0, sB0, 0);
-  SYNC();
-  SHIFT_DIAG(sA0, sB0, 0);
-  // first slice: no pending k-step from a previous slice
-  SLICE_STEP(sA0, sB0, sA1, sB1, true);
-  // Past the end the issue re-reads the last slice (never consumed), so every step has the same shape.
-  while (j + 1 < nk) {
-    SLICE_STEP(sA1, sB1, sA0, sB0, false);
-    SLICE_STEP(sA0, sB0, sA1, sB1, false);
+  if constexpr (!SYMSTORE) {
+    ISSUE(sA0, sB0, 0);
+    SYNC();
+    SHIFT_DIAG(sA0, sB0, 0);
+    // first slice: no pending k-step from a previous slice
+    SLICE_STEP(sA0, sB0, sA1, sB1, true);
+    // Past the end the issue re-reads the last slice (never consumed), so every step has the same shape.
+    while (j + 1 < nk) {
+      SLICE_STEP(sA1, sB1, sA0, sB0, false);
+      SLICE_STEP(sA0, sB0, sA1, sB1, false);
+    }
+    if (j < nk) SLICE_STEP(sA1, sB1, sA0, sB0, false);
+  } else {
+    // Operands are symmetric matrices of which only the 256 x 256 blocks on and above the diagonal
+    // hold valid data (M == N == K).  Block (r, c) with r > c is read as the transpose of block
+    // (c, r): its K slices are fetched k-row by k-row (the MN form).  With J1 / J2 the first slice
+    // of the tile's own row block / column block, the K walk has three phases,
+    //   [0, J1): A and B transposed;   [J1, J2): A as stored, B transposed;   [J2, nk): both as stored,
+    // each a multiple of four slices long, so every phase starts in stage 0; the last step of a
+    // phase issues the first slice of the next in that phase's form.
+    const int J1 = (m0 / 256) * 4, J2 = (n0 / 256) * 4;
+    operand_lane<true, TS> ma, mb;
+    ma.init(lane, wv, m0, M, P.lda, w_m * WM);
+    mb.init(lane, wv, n0, N, P.ldb, w_n * WN);
+    int vam[NLOAD], vbm[NLOAD];
+#pragma unroll
+    for (int q = 0; q < NLOAD; ++q) {
+      vam[q] = ma.voff[q];
+      vbm[q] = mb.voff[q];
+    }
+    const int ksam = __builtin_amdgcn_readfirstlane(ma.kstep), ksbm = __builtin_amdgcn_readfirstlane(mb.kstep);
+    // fragment set 1 starts as zeros, so the first step can run its "previous k-step" like any other
+#pragma unroll
+    for (int i = 0; i < FM; ++i) fa[1][i] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < FN; ++i) fb[1][i] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+#define ISSUE_MM(sa, sb, slice) ISSUE_V(sa, sb, slice, vam, ksam, vbm, ksbm)
+#define ISSUE_KM(sa, sb, slice) ISSUE_V(sa, sb, slice, va, ksa, vbm, ksbm)
+#define ISSUE_KK(sa, sb, slice) ISSUE_V(sa, sb, slice, va, ksa, vb, ksb)
+#define ISSUE_KKC(sa, sb, slice) ISSUE_KK(sa, sb, min((slice), nk - 1))
+#define ISSUE_AT(sa, sb, slice)                  \
+  {                                              \
+    if ((slice) < J1) {                          \
+      ISSUE_MM(sa, sb, slice);                   \
+    } else if ((slice) < J2) {                   \
+      ISSUE_KM(sa, sb, slice);                   \
+    } else {                                     \
+      ISSUE_KK(sa, sb, min((slice), nk - 1));    \
+    }                                            \
   }
-  if (j < nk) SLICE_STEP(sA1, sB1, sA0, sB0, false);
+#define STEP3(ca, cb, na, nb, LA, LB, ISSUE_NEXT)                         \
+  {                                                                       \
+    ISSUE_NEXT(na, nb, j + 1);                                            \
+    FETCH_L(0, ca, cb, 0, LA, LB);                                        \
+    SB();                                                                 \
+    MMA(1);                                                               \
+    SB();                                                                 \
+    FETCH_L(1, ca, cb, 1, LA, LB);                                        \
+    SB();                                                                 \
+    MMA(0);                                                               \
+    SB();                                                                 \
+    FETCH_L(0, ca, cb, 2, LA, LB);                                        \
+    SB();                                                                 \
+    MMA(1);                                                               \
+    SB();                                                                 \
+    FETCH_L(1, ca, cb, 3, LA, LB);                                        \
+    SB();                                                                 \
+    MMA(0);                                                               \
+    SB();                                                                 \
+    SYNC();                                                               \
+    ++j;                                                                  \
+    if (j < nk) SHIFT_DIAG(na, nb, j);                                    \
+  }
+#define PHASE3(LA, LB, ISSUE_SAME, jend)                                  \
+  if (j < (jend)) {                                                       \
+    while (j + 2 < (jend)) {                                              \
+      STEP3(sA0, sB0, sA1, sB1, LA, LB, ISSUE_SAME);                      \
+      STEP3(sA1, sB1, sA0, sB0, LA, LB, ISSUE_SAME);                      \
+    }                                                                     \
+    STEP3(sA0, sB0, sA1, sB1, LA, LB, ISSUE_SAME);                        \
+    STEP3(sA1, sB1, sA0, sB0, LA, LB, ISSUE_AT);                          \
+  }
+    ISSUE_AT(sA0, sB0, 0);
+    SYNC();
+    SHIFT_DIAG(sA0, sB0, 0);
+    PHASE3(ma, mb, ISSUE_MM, J1);
+    PHASE3(oa, mb, ISSUE_KM, J2);
+    // last phase: any number of slices; past the end the issue re-reads the last slice (never consumed)
+    STEP3(sA0, sB0, sA1, sB1, oa, ob, ISSUE_KKC);
+    while (j + 1 < nk) {
+      STEP3(sA1, sB1, sA0, sB0, oa, ob, ISSUE_KKC);
+      STEP3(sA0, sB0, sA1, sB1, oa, ob, ISSUE_KKC);
+    }
+    if (j < nk) STEP3(sA1, sB1, sA0, sB0, oa, ob, ISSUE_KKC);
+#undef PHASE3
+#undef STEP3
+#undef ISSUE_AT
+#undef ISSUE_KKC
+#undef ISSUE_KK
+#undef ISSUE_KM
+#undef ISSUE_MM
+  }
   MMA(1);  // k-step 3 of the last slice
 #undef SLICE_STEP
 #undef SHIFT_DIAG
 #undef SYNC
 #undef SB
 #undef FETCH
+#undef FETCH_L
 #undef MMA
 #undef ISSUE
+#undef ISSUE_V
 
   // ---- epilogue straight from the accumulators: a lane holds row m and 4 consecutive columns
   float s = 1.f;
@@ -321,7 +421,8 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
   const int elane = etid & 63, ewv = __builtin_amdgcn_readfirstlane(etid >> 6);  // wave-uniform
   const int e_m = ewv & 1, e_n = ewv >> 1;
   const int fr = elane & 31, fg = elane >> 5;
-  const bool mirror = SYM && (tm != tn);
+  // upper-only output (sym_store bit 1): the mirrored tile is written only inside a diagonal 256 x 256 block
+  const bool mirror = SYM && (tm != tn) && (!(args.sym_store & 2) || (m0 / 256 == n0 / 256));
   // The tile leaves through LDS so that every global store is a 16-byte piece of a row.  The four
   // stage arrays hold 64 tile rows each (rows of TS * 2 bytes, 16-byte chunk c of row r at slot
   // c ^ (r & (CPR - 1))).  The tile is staged once; it is read out row by row for C and, for an
@@ -480,6 +581,7 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
 // KIND 0: symmetric output, bf16 operands both KC or both MN; the upper triangle of tiles is computed.
 // KIND 1: general output, bf16 operands (A is KC; B is KC or MN).
 // KIND 2: symmetric output, half-precision operands, both KC.
+// KIND 3: as 2, with operands of which only the blocks on and above the diagonal are valid.
 template <int KIND, int TS>
 __global__ void __launch_bounds__(NTH) sm_ns_gemm_kernel(const sm_gemm_args args) {
   constexpr bool SYM = (KIND != 1);
@@ -533,8 +635,10 @@ __global__ void __launch_bounds__(NTH) sm_ns_gemm_kernel(const sm_gemm_args args
         gemm_tile<TS, false, false, false, false>(args, P, b, tm, tn, sA0, sA1, sB0, sB1);
       else
         gemm_tile<TS, false, true, false, false>(args, P, b, tm, tn, sA0, sA1, sB0, sB1);
-    } else {
+    } else if (KIND == 2) {
       gemm_tile<TS, false, false, true, true>(args, P, b, tm, tn, sA0, sA1, sB0, sB1);
+    } else {
+      gemm_tile<TS, false, false, true, true, true>(args, P, b, tm, tn, sA0, sA1, sB0, sB1);
     }
   }
 }
@@ -633,6 +737,8 @@ int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, bool sym, int klass) {
       return sm_fail(ctx, SM_EUNSUPPORTED, "internal: operand identity shift needs half-precision operands");
     if (args.in_f16 && (!sym || P.layout != 0))
       return sm_fail(ctx, SM_EUNSUPPORTED, "internal: half-precision GEMM operands need a symmetric K-contiguous product");
+    if (args.sym_store && (!args.in_f16 || P.M != P.K || P.N != P.K))
+      return sm_fail(ctx, SM_EUNSUPPORTED, "internal: upper-block storage needs square half-precision operands");
     // buffer offsets are 32-bit
     const long long a_ext = (P.layout & 1) ? (long long)P.K * P.lda : (long long)P.M * P.lda;
     const long long b_ext = (P.layout & 2) ? (long long)P.K * P.ldb : (long long)P.N * P.ldb;
@@ -673,7 +779,11 @@ int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, bool sym, int klass) {
   }
   {
     sm_launch_scope sc(ctx, klass);
-    if (args.in_f16 && ts == 256)
+    if (args.in_f16 && (args.sym_store & 1) && ts == 256)
+      hipLaunchKernelGGL((sm_ns_gemm_kernel<3, 256>), grid, block, 0, ctx->stream, args);
+    else if (args.in_f16 && (args.sym_store & 1))
+      hipLaunchKernelGGL((sm_ns_gemm_kernel<3, 128>), grid, block, 0, ctx->stream, args);
+    else if (args.in_f16 && ts == 256)
       hipLaunchKernelGGL((sm_ns_gemm_kernel<2, 256>), grid, block, 0, ctx->stream, args);
     else if (args.in_f16)
       hipLaunchKernelGGL((sm_ns_gemm_kernel<2, 128>), grid, block, 0, ctx->stream, args);
