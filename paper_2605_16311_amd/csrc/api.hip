@@ -380,6 +380,7 @@ int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const
     g.klass = SM_K_NS_GRAM;
     g.scale_pow = sc ? 2 : 0;
     g.out_f16 = (kk > 1);
+    g.sym_store = (kk > 1) ? (ss & 2) : 0;  // A_0 is only read by the products below
     if (kk == 1) {  // only P_1 = Q_0 is needed, in bf16
       g.alpha = b;
       g.diag = a;

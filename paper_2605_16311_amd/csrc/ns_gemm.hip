@@ -737,8 +737,10 @@ int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, bool sym, int klass) {
       return sm_fail(ctx, SM_EUNSUPPORTED, "internal: operand identity shift needs half-precision operands");
     if (args.in_f16 && (!sym || P.layout != 0))
       return sm_fail(ctx, SM_EUNSUPPORTED, "internal: half-precision GEMM operands need a symmetric K-contiguous product");
-    if (args.sym_store && (!args.in_f16 || P.M != P.K || P.N != P.K))
-      return sm_fail(ctx, SM_EUNSUPPORTED, "internal: upper-block storage needs square half-precision operands");
+    if ((args.sym_store & 1) && (!args.in_f16 || P.M != P.K || P.N != P.K))
+      return sm_fail(ctx, SM_EUNSUPPORTED, "internal: upper-block operands need a square half-precision product");
+    if ((args.sym_store & 2) && !sym)
+      return sm_fail(ctx, SM_EUNSUPPORTED, "internal: upper-block output needs a symmetric product");
     // buffer offsets are 32-bit
     const long long a_ext = (P.layout & 1) ? (long long)P.K * P.lda : (long long)P.M * P.lda;
     const long long b_ext = (P.layout & 2) ? (long long)P.K * P.ldb : (long long)P.N * P.ldb;
