@@ -774,9 +774,20 @@ int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, bool sym, int klass) {
       const double mnk = (double)P.M * P.N * P.K * P.batch;
       ctx->work_flop[klass] += 2.0 * mnk;
       const bool same = (P.A == P.B);
-      ctx->work_bytes[klass] += 2.0 * P.batch * ((double)P.M * P.K + (same ? 0.0 : (double)P.N * P.K) +
-                                                 (double)P.M * P.N * ((P.C != nullptr) + (P.R != nullptr && P.R != P.A && P.R != P.B))) +
-                             (P.sign_out ? (double)P.batch * P.sign_stride : 0.0);
+      // upper-block storage: the share of an s x s matrix that lies in its 256 x 256 blocks on and above the diagonal
+      auto upper_share = [](int s) {
+        double kept = 0.0;
+        for (int r = 0; r < s; r += 256) kept += (double)std::min(256, s - r) * (s - r);
+        return kept / ((double)s * s);
+      };
+      const double in_share = (args.sym_store & 1) ? upper_share(P.K) : 1.0;
+      const double out_share = (args.sym_store & 2) ? upper_share(P.M) : 1.0;
+      const double r_share = (args.sym_store & 2) ? out_share : 1.0;  // R is read where the output is written
+      ctx->work_bytes[klass] +=
+          2.0 * P.batch * (in_share * ((double)P.M * P.K + (same ? 0.0 : (double)P.N * P.K)) +
+                           (double)P.M * P.N * (out_share * (P.C != nullptr) +
+                                                r_share * (P.R != nullptr && P.R != P.A && P.R != P.B))) +
+          (P.sign_out ? (double)P.batch * P.sign_stride : 0.0);
     }
   }
   {
