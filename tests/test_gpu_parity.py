@@ -293,6 +293,9 @@ NS_CASES = [
     (2, 448, 192, 9, "fro", O.PAPER_COEFFS),        # segments 5 + 4: two pairs, tall
     (2, 256, 384, 5, "fro", (1.25, -0.4, 0.0)),     # another cubic on the short-side recurrence
     (2, 256, 384, 4, "none", (1.4, -0.45, 0.0)),
+    (2, 320, 512, 5, "fro", O.PAPER_COEFFS),        # short side 320: a whole and a partial 256-block
+    (1, 640, 576, 5, "fro", O.PAPER_COEFFS),        # short side 576 (tall): three blocks, the last partial
+    (1, 640, 640, 4, "fro", O.PAPER_COEFFS),        # square, 2.5 blocks
 ]
 
 
