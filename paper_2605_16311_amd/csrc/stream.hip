@@ -69,7 +69,7 @@ __global__ void __launch_bounds__(TPB) sm_momentum_kernel(const mom_args a) {
     for (int it = 0; it < SM_MOM_CHUNK / (TPB * 4); ++it) {
       const long long i = base + (long long)it * (TPB * 4) + threadIdx.x * 4;
       if (i >= d) break;  // d % 4 == 0 on this path
-      f32x4 m = *reinterpret_cast<const f32x4*>(mom + i);
+      f32x4 m = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(mom + i));
       const f32x4 g = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(grad + i));
       f32x4 ww = {0.f, 0.f, 0.f, 0.f};
       if (has_wd) ww = *reinterpret_cast<const f32x4*>(w + i);
@@ -506,13 +506,13 @@ __global__ void __launch_bounds__(TPB) sm_update_kernel(const upd_args g) {
   const long long base = (long long)(blockIdx.x - D.block_begin) * UPD_CHUNK + threadIdx.x * 4;
   if ((cols & 3) == 0 && base - threadIdx.x * 4 + UPD_CHUNK <= n) {  // a full chunk of whole groups of 4
     bf16x4 h[UPD_ITERS];
-    float4 wv[UPD_ITERS];
+    f32x4 wv[UPD_ITERS];
 #pragma unroll
     for (int it = 0; it < UPD_ITERS; ++it) {
       const long long e0 = base + (long long)it * (TPB * 4);
       const long long di4 = (ld == cols) ? e0 : (e0 / cols) * ld + (e0 % cols);
-      h[it] = *reinterpret_cast<const bf16x4*>(d + di4);
-      wv[it] = *reinterpret_cast<const float4*>(w + e0);
+      h[it] = __builtin_nontemporal_load(reinterpret_cast<const bf16x4*>(d + di4));
+      wv[it] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(w + e0));
     }
 #pragma unroll
     for (int it = 0; it < UPD_ITERS; ++it) {
@@ -521,7 +521,7 @@ __global__ void __launch_bounds__(TPB) sm_update_kernel(const upd_args g) {
       wv[it].y = __fsub_rn(wv[it].y, __fmul_rn(step, (float)h[it][1]));
       wv[it].z = __fsub_rn(wv[it].z, __fmul_rn(step, (float)h[it][2]));
       wv[it].w = __fsub_rn(wv[it].w, __fmul_rn(step, (float)h[it][3]));
-      *reinterpret_cast<float4*>(w + e0) = wv[it];
+      __builtin_nontemporal_store(wv[it], reinterpret_cast<f32x4*>(w + e0));
     }
     return;
   }
