@@ -421,6 +421,61 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
   const int elane = etid & 63, ewv = __builtin_amdgcn_readfirstlane(etid >> 6);  // wave-uniform
   const int e_m = ewv & 1, e_n = ewv >> 1;
   const int fr = elane & 31, fg = elane >> 5;
+  if constexpr (!SYM) {
+    // Only the packed 1-bit signs of the tile are wanted (the apply before the vote): they are taken
+    // straight from the accumulators.  A lane holds, per 32 x 32 fragment, 16 entries of one row:
+    // columns 8 vg + 4 fg + e of the fragment's 32.  For every value but -0, a negative denormal
+    // and NaN, "the bf16 rounding of x is >= 0" is just "the sign bit of x is clear", which one
+    // alignbit shifts into a word; a wave that meets one of those three recomputes its bits from
+    // the rounded values, so the result is that of the staged path bit for bit.
+    if (!C && P.sign_out && P.sign_fmt == SM_SIGN_1BIT && args.diag == 0.f && !of16) {
+      unsigned words[FM][FN];
+      bool rare = false;
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < FN; ++jn) {
+          unsigned neg = 0;
+#pragma unroll
+          for (int v = 15; v >= 0; --v) {
+            const float o = alpha * acc[i][jn][v];
+            rare |= __builtin_amdgcn_classf(o, 0x33);  // sNaN, qNaN, -denormal, -0
+            neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(o), 31);
+          }
+          words[i][jn] = ~neg & 0xFFFFu;  // bit 4 vg + e
+        }
+      if (__builtin_amdgcn_ballot_w64(rare) != 0) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+          for (int jn = 0; jn < FN; ++jn) {
+            unsigned bits = 0;
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) {
+              const unsigned h = pack2(alpha * acc[i][jn][v], alpha * acc[i][jn][v + 1], false);
+              bits |= (ge0_bf16(h & 0xFFFFu) << v) | (ge0_bf16(h >> 16) << (v + 1));
+            }
+            words[i][jn] = bits;
+          }
+      }
+      unsigned char* so = reinterpret_cast<unsigned char*>(P.sign_out) + (long long)b * P.sign_stride;
+#pragma unroll
+      for (int i = 0; i < FM; ++i) {
+        const int mg = m0 + e_m * WM + i * 32 + fr;
+#pragma unroll
+        for (int jn = 0; jn < FN; ++jn) {
+          // nibble vg -> bits 8 vg + 4 fg .. + 3; the lane 32 further holds the other half of the word
+          const unsigned x = words[i][jn];
+          unsigned w = ((x & 0xFu) | ((x & 0xF0u) << 4) | ((x & 0xF00u) << 8) | ((x & 0xF000u) << 12)) << (4 * fg);
+          w |= __shfl_xor(w, 32, 64);
+          const int c0 = n0 + e_n * WN + jn * 32;
+          if ((jn & 1) == fg && mg < P.sign_rows && c0 < P.sign_cols)  // sign_cols % 32 == 0: a word is live as a whole
+            *reinterpret_cast<unsigned*>(so + (((long long)mg * P.sign_cols + c0) >> 3)) = w;
+        }
+      }
+      return;
+    }
+  }
   // upper-only output (sym_store bit 1): the mirrored tile is written only inside a diagonal 256 x 256 block
   const bool mirror = SYM && (tm != tn) && (!(args.sym_store & 2) || (m0 / 256 == n0 / 256));
   // The tile leaves through LDS so that every global store is a 16-byte piece of a row.  The four
