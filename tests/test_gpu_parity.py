@@ -404,16 +404,26 @@ def test_step_mixed_set(P, ctx, sign_fmt, Kp):
     run_step_case(P, ctx, shapes, 3, sign_fmt=sign_fmt, Kp=Kp, wd=0.1, rsqrt=(Kp > 0))
 
 
-def test_step_signs_written_by_the_apply_alone(P, ctx):
-    """Without a u_out tap the last apply writes only the packed signs (U is never stored).  The same step
-    with all taps (checked against the oracle by the cases above) must give the same signs, counts and W."""
+@pytest.mark.parametrize("special", [False, True])
+def test_step_signs_written_by_the_apply_alone(P, ctx, special):
+    """Without a u_out tap the last apply writes only the packed signs (U is never stored; the bits come
+    straight from the accumulators).  The same step with all taps (checked against the oracle by the cases
+    above; there the signs are taken from the stored bf16 U) must give the same signs, counts and W.
+    special: a column of entries near the bottom of the fp32 range (its outputs fall among the
+    denormals, negative ones included), a NaN (the whole matrix turns NaN: all signs -1) and a zero matrix."""
     # (64, 100) cannot be packed by the GEMM; (200, 160) is packed with padding in both dimensions
     shapes, M = [(128, 256), (256, 128), (192, 192), (64, 100), (200, 160)], 3
     outs = []
     for tapped in (True, False):
         w = [dev(wl.weights(r, c, block=i)) for i, (r, c) in enumerate(shapes)]
         mom = [torch.zeros((M, r, c), device="cuda") for r, c in shapes]
-        grad = [dev(wl.normal((M, r, c), stream=29, block=i)) for i, (r, c) in enumerate(shapes)]
+        g_host = [wl.normal((M, r, c), stream=29, block=i) for i, (r, c) in enumerate(shapes)]
+        if special:
+            sgn = np.where(wl.normal((M, 128), stream=30) >= 0, 1.0, -1.0).astype(np.float32)
+            g_host[0][:, :, 5] = sgn * np.float32(3e-37)
+            g_host[1][0, 7, 9] = np.float32("nan")
+            g_host[2][1] = 0.0
+        grad = [dev(g) for g in g_host]
         d = [r * c for r, c in shapes]
         signs = [torch.zeros((M, O.packed_stride_bytes(x)), dtype=torch.uint8, device="cuda") for x in d]
         counts = [torch.zeros((x,), dtype=torch.int32, device="cuda") for x in d]
