@@ -49,6 +49,7 @@
 // operand form (MN for the transposed blocks, KC for the stored ones) at block boundaries.
 // A third fewer bytes go to and come from memory, which is what bounds those products.
 #include "common.h"
+#include <type_traits>
 
 namespace sm_gemm {
 
@@ -503,28 +504,40 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
     return w;
   };
   auto stage = [&](int idx) -> unsigned char* { return idx == 0 ? sA0 : idx == 1 ? sA1 : idx == 2 ? sB0 : sB1; };
+  // the staging loop in four forms: with or without the check for diagonal entries (only tiles that
+  // meet the diagonal of a product with a diag term need it) and for either output type, so that
+  // neither costs vector instructions per entry where it does not apply
+  auto stage_tile = [&](auto on_diag, auto half) {
+    constexpr bool ON_DIAG = decltype(on_diag)::value, HALF = decltype(half)::value;
 #pragma unroll
-  for (int i = 0; i < FM; ++i) {
-    const int ml = e_m * WM + i * 32 + fr;  // tile row of this lane
-    const int mg = m0 + ml;
-    // rows e_m*WM + i*32 .. +31 lie in one stage array (64 rows each): uniform choice
-    unsigned char* sp = stage((e_m * WM + i * 32) >> 6);
+    for (int i = 0; i < FM; ++i) {
+      const int ml = e_m * WM + i * 32 + fr;  // tile row of this lane
+      const int mg = m0 + ml;
+      // rows e_m*WM + i*32 .. +31 lie in one stage array (64 rows each): uniform choice
+      unsigned char* sp = stage((e_m * WM + i * 32) >> 6);
 #pragma unroll
-    for (int jn = 0; jn < FN; ++jn) {
+      for (int jn = 0; jn < FN; ++jn) {
 #pragma unroll
-      for (int vg = 0; vg < 4; ++vg) {
-        const int nl = e_n * WN + jn * 32 + 8 * vg + 4 * fg;  // first of 4 tile columns
-        const int ng = n0 + nl;
-        float o[4];
+        for (int vg = 0; vg < 4; ++vg) {
+          const int nl = e_n * WN + jn * 32 + 8 * vg + 4 * fg;  // first of 4 tile columns
+          const int ng = n0 + nl;
+          float o[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          o[e] = alpha * acc[i][jn][4 * vg + e];
-          if (mg == ng + e) o[e] += args.diag;
+          for (int e = 0; e < 4; ++e) {
+            o[e] = alpha * acc[i][jn][4 * vg + e];
+            if (ON_DIAG && mg == ng + e) o[e] += args.diag;
+          }
+          const u32x2 h = {pack2(o[0], o[1], HALF), pack2(o[2], o[3], HALF)};
+          *reinterpret_cast<u32x2*>(sp + (ml & 63) * RB + ((((nl >> 3) ^ (ml & (CPR - 1)))) << 4) + (nl & 7) * 2) = h;
         }
-        const u32x2 h = {pack2(o[0], o[1], of16), pack2(o[2], o[3], of16)};
-        *reinterpret_cast<u32x2*>(sp + (ml & 63) * RB + ((((nl >> 3) ^ (ml & (CPR - 1)))) << 4) + (nl & 7) * 2) = h;
       }
     }
+  };
+  const bool diag_tile = args.diag != 0.f && m0 < n0 + TS && n0 < m0 + TS;
+  if (diag_tile) {
+    if (of16) stage_tile(std::true_type{}, std::true_type{}); else stage_tile(std::true_type{}, std::false_type{});
+  } else {
+    if (of16) stage_tile(std::false_type{}, std::true_type{}); else stage_tile(std::false_type{}, std::false_type{});
   }
   __syncthreads();
   if (SYM || C) {
