@@ -489,17 +489,26 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
   const bf16_t* __restrict__ R = P.R ? P.R + (long long)b * P.sC : nullptr;
   const bool rf16 = args.r_f16 != 0;
   const float gamma = args.gamma;
-  // 8 staged outputs + gamma times 8 elements of R, rounded again
+  // 8 staged outputs + gamma times 8 elements of R, rounded again.  When both are half precision and
+  // gamma is a half-precision number (the paper's coefficients give -0.5390625), packed
+  // half-precision fmas do it with a single rounding and no conversions.
+  const _Float16 gamma_h = (_Float16)gamma;
+  const int r_mode = (of16 && rf16 && (float)gamma_h == gamma) ? 2 : (of16 ? 1 : 0) | (rf16 ? 4 : 0);
   auto add_r = [&](u32x4 v, u32x4 a) -> u32x4 {
+    if (r_mode == 2) {
+      const f16x8 g8 = {gamma_h, gamma_h, gamma_h, gamma_h, gamma_h, gamma_h, gamma_h, gamma_h};
+      return __builtin_bit_cast(u32x4, __builtin_elementwise_fma(g8, __builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, v)));
+    }
+    const bool o16 = (r_mode & 1) != 0, r16 = (r_mode & 4) != 0;
     u32x4 w;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       float lo, hi, alo, ahi;
-      unpack2(v[q], of16, lo, hi);
-      unpack2(a[q], rf16, alo, ahi);
+      unpack2(v[q], o16, lo, hi);
+      unpack2(a[q], r16, alo, ahi);
       lo += gamma * alo;
       hi += gamma * ahi;
-      w[q] = pack2(lo, hi, of16);
+      w[q] = pack2(lo, hi, o16);
     }
     return w;
   };
