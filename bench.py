@@ -98,15 +98,18 @@ def run_workload(name, steps, warmup, torch, P, B, scale=None):
     gemm = {}
     for k in gemm_classes:
         n, ms = ctx.profile_read(k)
-        flop, nbytes = ctx.profile_work(k)
+        flop, dense, nbytes = ctx.profile_work(k)
         if n == 0:
             continue
         sec = ms * 1e-3
         t_mfma, t_hbm = flop / (MFMA_BF16_PEAK_TFLOPS * 1e12), nbytes / (HBM_PEAK_GBS * 1e9)
+        # flop: the output tiles the launches really computed (a symmetric product: the tiles on and above
+        # the diagonal; sizes clipped to the unpadded matrices).  dense: 2 M N K of the same products.
         gemm[P.kernel_name(k)] = {
             "launches_per_step": n / steps, "avg_launch_ms": ms / n, "ms_per_step": ms / steps,
-            "flop_per_launch": flop / n, "bytes_per_launch": nbytes / n,
-            "tflops": flop / sec / 1e12, "gbs": nbytes / sec / 1e9,
+            "flop_per_launch": flop / n, "dense_flop_per_launch": dense / n, "bytes_per_launch": nbytes / n,
+            "tflops": flop / sec / 1e12, "frac_of_mfma_peak": flop / sec / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "dense_equiv_tflops": dense / sec / 1e12, "gbs": nbytes / sec / 1e9,
             "bound": "mfma" if t_mfma >= t_hbm else "hbm",
         }
     # second, untimed pass with taps on every kernel class: per-class breakdown
@@ -143,10 +146,11 @@ def run_workload(name, steps, warmup, torch, P, B, scale=None):
         "workload": name, "M": M, "n_blocks": len(shapes), "entries": d_total, "ns_steps": K,
         "local_polar_steps": Kp, "scale": scale,
         "steps_per_s": steps / elapsed, "ms_per_step": 1e3 * elapsed / steps,
-        # nominal: the work of Alg. PolarNS as written (4 s^2 l per step and matrix) over the time of all
-        # Newton-Schulz launches; executed: the matrix products actually launched
-        "ns_tflops": nominal / (ns_ms * 1e-3) / 1e12 if ns_ms else None,
+        # executed: the matrix-product tiles actually computed, over the time of all Newton-Schulz launches (the
+        # utilisation figure); nominal: the work of Alg. PolarNS as written (4 s^2 l per step and matrix) over the
+        # same time, i.e. the rate a step-by-step implementation would need to be as fast (not a utilisation)
         "ns_tflops_executed": executed / (ns_ms * 1e-3) / 1e12 if ns_ms else None,
+        "ns_nominal_tflops": nominal / (ns_ms * 1e-3) / 1e12 if ns_ms else None,
         "ns_ms_per_step": ns_ms, "gemm": gemm,
         # the sign pack is part of the last apply GEMM when its class reports no launches: then only the
         # vote's own bytes and time are counted here
@@ -235,6 +239,14 @@ def cpu_baseline(name, budget_s=15.0):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
+    cpu_model = "unknown"
+    try:
+        for ln in open("/proc/cpuinfo"):
+            if ln.lower().startswith("model name"):
+                cpu_model = ln.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
     cfg = wl.WORKLOADS[name]
     shapes, M = cfg["shapes"], cfg["M"]
     # Blocks and workers are independent, so the step time is the sum over blocks.  Blocks of the
@@ -265,7 +277,7 @@ def cpu_baseline(name, budget_s=15.0):
         if t_spent > budget_s and n_done >= len(seen):
             break
     step_s = t_spent * total_flop / flop_done
-    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": int(cores), "cpu_model": cpu_model, "kind": "oracle",
             "sample": f"float32 oracle (numpy), full per-block step on {n_done} of {len(shapes)} blocks "
                       f"(every distinct shape, all {M} workers) in {t_spent:.1f} s, scaled to the whole set "
                       f"by nominal Newton-Schulz work"}
@@ -277,8 +289,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="nanogpt124m")
-    ap.add_argument("--also", default="resnet50,nanogpt_paper_k10,resnet50_k1",
-                    help="further workloads (comma separated) reported in the same line under 'also' ('' to skip)")
+    ap.add_argument("--also", default="resnet50,nanogpt_paper_k10,resnet50_k1,large,int8vote",
+                    help="further workloads (comma separated) reported in the same line under 'also' ('' to skip); "
+                         "the two large sets run 3 timed steps, the small ones 5 x --steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--scale", default=None, choices=["fro", "spectral"],
                     help="scale of Alg. PolarNS: Frobenius norm or PowerIter with P = 2 (default: the workload's own)")
@@ -306,7 +319,8 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
     main_res = run_workload(args.workload, args.steps, args.warmup, torch, P, B, scale=args.scale)
-    also = [run_workload(nm, max(args.steps * 5, 50), args.warmup, torch, P, B)
+    big = ("large", "int8vote")             # a quarter and an eighth of a second per step
+    also = [run_workload(nm, 3 if nm in big else max(args.steps * 5, 50), 1 if nm in big else args.warmup, torch, P, B)
             for nm in args.also.split(",") if nm and nm != args.workload]
     # roofline of the dominant kernel: the GEMM class with the largest share of the step
     dom_name, dom = max(main_res["gemm"].items(), key=lambda kv: kv[1]["ms_per_step"])
@@ -317,6 +331,7 @@ def main():
             traffic = json.load(open(tpath)).get(args.workload, {}).get(dom_name)
         except Exception:
             traffic = None
+    # bound by the matrix cores: achieved = executed flop (tiles really computed) per launch / launch duration
     if dom["bound"] == "mfma":
         ach, peak, unit = dom["tflops"], MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
     else:
@@ -336,16 +351,24 @@ def main():
         "roofline": {"kernel": dom_name, "bound": dom["bound"], "achieved": ach, "peak": peak, "unit": unit,
                      "frac": ach / peak, "traffic": traffic, "avg_launch_ms": dom["avg_launch_ms"],
                      "flop_per_launch": dom["flop_per_launch"], "bytes_per_launch": dom["bytes_per_launch"]},
-        "ns": {"tflops": main_res["ns_tflops"],
-               "frac_of_mfma_peak": main_res["ns_tflops"] / MFMA_BF16_PEAK_TFLOPS if main_res["ns_tflops"] else None,
-               "tflops_executed": main_res["ns_tflops_executed"], "ms_per_step": main_res["ns_ms_per_step"],
+        # tflops / frac_of_mfma_peak: executed tile flop of all Newton-Schulz launches over their time;
+        # nominal_tflops: Alg. PolarNS's 4 s^2 l per step and matrix over the same time (algorithm-equivalent rate of
+        # the regrouped iteration, which executes about half of that work: a speed figure, not a utilisation)
+        "ns": {"tflops": main_res["ns_tflops_executed"],
+               "frac_of_mfma_peak": (main_res["ns_tflops_executed"] / MFMA_BF16_PEAK_TFLOPS
+                                     if main_res["ns_tflops_executed"] else None),
+               "nominal_tflops": main_res["ns_nominal_tflops"], "ms_per_step": main_res["ns_ms_per_step"],
                "gemm": main_res["gemm"]},
         # standalone: signmuon_sign_pack + signmuon_majority_vote on their own over the whole set (the figure the
         # HBM target is quoted on); in_step: what the step itself ran (the pack rides in the apply when fused)
         "sign_vote": {"gbs": main_res["standalone"]["sign_vote_gbs"],
                       "frac_of_hbm_peak": main_res["standalone"]["sign_vote_gbs"] / HBM_PEAK_GBS,
+                      "sign_pack_frac_of_hbm_peak": main_res["standalone"]["sign_pack_gbs"] / HBM_PEAK_GBS,
+                      "vote_frac_of_hbm_peak": main_res["standalone"]["vote_gbs"] / HBM_PEAK_GBS,
                       "standalone": main_res["standalone"],
                       "in_step_gbs": main_res["sign_vote_gbs"],
+                      "in_step_frac_of_hbm_peak": (main_res["sign_vote_gbs"] / HBM_PEAK_GBS
+                                                   if main_res["sign_vote_gbs"] else None),
                       "sign_pack_fused_into_apply": main_res["sign_pack_fused_into_apply"]},
         "momentum_gbs": main_res["momentum_gbs"],
         "per_class_ms": {k: round(v["ms_per_step"], 4) for k, v in main_res["per_class"].items()},
@@ -356,8 +379,17 @@ def main():
         line["also"] = []
         for a in also:
             e = {k: a[k] for k in ("workload", "M", "n_blocks", "ns_steps", "local_polar_steps", "scale", "steps_per_s",
-                                   "ms_per_step", "graph_replay", "ns_tflops", "ns_tflops_executed", "momentum_gbs")}
+                                   "ms_per_step", "graph_replay", "ns_tflops_executed", "ns_nominal_tflops",
+                                   "momentum_gbs")}
+            e["ns_frac_of_mfma_peak"] = (a["ns_tflops_executed"] / MFMA_BF16_PEAK_TFLOPS
+                                         if a["ns_tflops_executed"] else None)
+            e["gemm"] = {k: {"avg_launch_ms": v["avg_launch_ms"], "launches_per_step": v["launches_per_step"],
+                             "tflops": v["tflops"], "frac_of_mfma_peak": v["frac_of_mfma_peak"]}
+                         for k, v in a["gemm"].items()}
             e["sign_vote_gbs"] = a["standalone"]["sign_vote_gbs"]
+            e["sign_pack_gbs"] = a["standalone"]["sign_pack_gbs"]
+            e["vote_gbs"] = a["standalone"]["vote_gbs"]
+            e["in_step_sign_vote_gbs"] = a["sign_vote_gbs"]
             e["per_class_ms"] = {k: round(v["ms_per_step"], 4) for k, v in a["per_class"].items()}
             line["also"].append(e)
     if not args.no_cpu_baseline:

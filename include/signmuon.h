@@ -21,8 +21,10 @@
  *   - Return value: SM_OK (0) or a negative SM_E* code.  Arguments are checked
  *     on the host before anything is launched; on error nothing has been
  *     queued.  signmuon_last_error gives the text of the last failure.
- *   - fp32 matrices must be 16-byte aligned, bf16 matrices 16-byte aligned,
- *     packed sign buffers 8-byte aligned.
+ *   - Alignment: signmuon_step needs 16-byte aligned blocks; the single-stage
+ *     calls accept element-aligned matrices (4 bytes fp32, 2 bytes bf16) and run
+ *     their vector paths when pointers and sizes allow 16-byte accesses; packed
+ *     sign buffers are 8-byte aligned.
  *   - Results are deterministic: no floating-point atomics are used.
  */
 #ifndef SIGNMUON_H
@@ -68,10 +70,30 @@ typedef struct signmuon_ctx signmuon_ctx; /* opaque; owns only its own workspace
 /* ---- context ---------------------------------------------------------- */
 
 /* Creates a context bound to the current HIP device and to `hip_stream`
- * (a hipStream_t; NULL = the default stream).  *out is set on success. */
-int signmuon_create(signmuon_ctx** out, void* hip_stream);
+ * (a hipStream_t; NULL = the default stream).  *out is set on success.
+ * workspace_bytes_hint: device bytes to reserve for signmuon_step's workspace right
+ * away (0 = none).  The workspace is otherwise sized by the first signmuon_step /
+ * signmuon_polar_ns call for a new set of shapes, which allocates, clears it and
+ * may wait for the stream: such a first call must not be captured into a HIP graph.
+ * Later calls for the same shapes only queue kernels. */
+int signmuon_create(signmuon_ctx** out, void* hip_stream, size_t workspace_bytes_hint);
 /* Waits for the stream, frees the context's workspaces. */
 int signmuon_destroy(signmuon_ctx* ctx);
+
+/* Tuning switches of a context.  Every setting computes the same path within the
+ * same tolerances; they exist for measurements and tests.  Values other than the
+ * listed ones give SM_EINVAL. */
+#define SM_OPT_GEMM_TILE 0 /* workgroup tile of the Newton-Schulz GEMMs: 0 = by launch size (default), 128, 256 */
+#define SM_OPT_NS_PATH 1   /* how the K steps of the cubic iteration are grouped: */
+#define SM_NS_PATH_PAIRS 0    /*   short-side recurrence, two steps per quartic (default) */
+#define SM_NS_PATH_SINGLE 1   /*   short-side recurrence, one step at a time */
+#define SM_NS_PATH_STEPWISE 2 /*   Alg. PolarNS as written: Gram and apply of Y per step */
+#define SM_OPT_NS_STORE 2  /* storage of the symmetric s x s matrices of the recurrence: */
+#define SM_NS_STORE_UPPER 0   /*   blocks on and above the diagonal only (default) */
+#define SM_NS_STORE_FULL 1    /*   whole matrices */
+#define SM_OPT_COUNT 3
+int signmuon_set_option(signmuon_ctx* ctx, int option, int value);
+int signmuon_get_option(const signmuon_ctx* ctx, int option, int* value);
 /* Static text for a status code. */
 const char* signmuon_strerror(int status);
 /* Text of the last error on this context ("" if none).  HOST string owned by ctx. */
@@ -190,10 +212,16 @@ int signmuon_profile_enable(signmuon_ctx* ctx, unsigned class_mask);
 int signmuon_profile_reset(signmuon_ctx* ctx);
 int signmuon_profile_read(signmuon_ctx* ctx, int kernel_class, int64_t* launches, double* total_ms);
 /* Work booked by the timed launches of a GEMM class since the last reset:
- * flop = sum of 2*M*N*K over the matrix products as written (a symmetric product
- * counts in full although only its upper triangle of tiles is computed), bytes =
- * their operands and results, each counted once.  Zero for the other classes. */
-int signmuon_profile_work(signmuon_ctx* ctx, int kernel_class, double* flop, double* bytes);
+ * flop_executed = 2 * rows * cols * K summed over the output tiles the launch really
+ *   computes (for a symmetric product: the tiles on and above the diagonal), with rows,
+ *   cols and K clipped to the logical (unpadded) sizes;
+ * flop_dense = 2*M*N*K over the same products as written (what a kernel without the
+ *   symmetry saving would execute);
+ * bytes = their operands and results, each counted once (its stored share for a
+ *   symmetric matrix kept in upper-block storage).
+ * Zero for the other classes.  Any of the three pointers may be NULL. */
+int signmuon_profile_work(signmuon_ctx* ctx, int kernel_class, double* flop_executed, double* flop_dense,
+                          double* bytes);
 const char* signmuon_kernel_name(int kernel_class);
 
 #ifdef __cplusplus

@@ -28,9 +28,15 @@ SCALES = {"fro": SM_SCALE_FRO, "spectral": SM_SCALE_SPECTRAL, "none": SM_SCALE_N
 SIGN_FMTS = {"1bit": SM_SIGN_1BIT, "int8": SM_SIGN_INT8}
 VOTE_FMTS = {"bits": SM_VOTE_BITS, "int8": SM_VOTE_INT8, "bf16": SM_VOTE_BF16, "f32": SM_VOTE_F32}
 
+SM_OPT_GEMM_TILE, SM_OPT_NS_PATH, SM_OPT_NS_STORE = 0, 1, 2
+NS_PATHS = {"pairs": 0, "single": 1, "stepwise": 2}
+NS_STORES = {"upper": 0, "full": 1}
+
 EXPORTS = [
-    "signmuon_create", "signmuon_destroy", "signmuon_strerror", "signmuon_last_error",
-    "signmuon_workspace_bytes", "signmuon_momentum", "signmuon_polar_ns", "signmuon_sign_pack",
+    "signmuon_create", "signmuon_destroy", "signmuon_set_option", "signmuon_get_option",
+    "signmuon_strerror", "signmuon_last_error",
+    "signmuon_workspace_bytes", "signmuon_momentum", "signmuon_polar_ns",
+    "signmuon_sign_pack",
     "signmuon_majority_vote", "signmuon_step", "signmuon_profile_enable", "signmuon_profile_reset",
     "signmuon_profile_read", "signmuon_profile_work", "signmuon_kernel_name",
 ]
@@ -57,8 +63,10 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         raise ImportError(f"{path} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
     lib = C.CDLL(path)
     vp, i32, i64, f32 = C.c_void_p, C.c_int, C.c_int64, C.c_float
-    lib.signmuon_create.argtypes = [C.POINTER(vp), vp]
+    lib.signmuon_create.argtypes = [C.POINTER(vp), vp, C.c_size_t]
     lib.signmuon_destroy.argtypes = [vp]
+    lib.signmuon_set_option.argtypes = [vp, i32, i32]
+    lib.signmuon_get_option.argtypes = [vp, i32, C.POINTER(i32)]
     lib.signmuon_strerror.argtypes = [i32]
     lib.signmuon_strerror.restype = C.c_char_p
     lib.signmuon_last_error.argtypes = [vp]
@@ -73,7 +81,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.signmuon_profile_enable.argtypes = [vp, C.c_uint]
     lib.signmuon_profile_reset.argtypes = [vp]
     lib.signmuon_profile_read.argtypes = [vp, i32, C.POINTER(i64), C.POINTER(C.c_double)]
-    lib.signmuon_profile_work.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.signmuon_profile_work.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                          C.POINTER(C.c_double)]
     lib.signmuon_kernel_name.argtypes = [i32]
     lib.signmuon_kernel_name.restype = C.c_char_p
     return lib
@@ -107,15 +116,27 @@ def _dtype_code(t):
 class Context:
     """signmuon_ctx bound to torch's current stream on the current device."""
 
-    def __init__(self, stream: "torch.cuda.Stream | None" = None):
+    def __init__(self, stream: "torch.cuda.Stream | None" = None, workspace_bytes_hint: int = 0, *,
+                 gemm_tile: int = 0, ns_path: str = "pairs", ns_store: str = "upper"):
         if not torch.cuda.is_available():
             raise SignMuonError("no HIP device: libsignmuon has no CPU path")
         self.stream = stream if stream is not None else torch.cuda.current_stream()
         h = C.c_void_p()
-        rc = _lib.signmuon_create(C.byref(h), C.c_void_p(self.stream.cuda_stream))
+        rc = _lib.signmuon_create(C.byref(h), C.c_void_p(self.stream.cuda_stream), int(workspace_bytes_hint))
         if rc != SM_OK:
             raise SignMuonError(f"signmuon_create: {_lib.signmuon_strerror(rc).decode()}")
         self._h = h
+        self.set_option(SM_OPT_GEMM_TILE, gemm_tile)
+        self.set_option(SM_OPT_NS_PATH, NS_PATHS[ns_path])
+        self.set_option(SM_OPT_NS_STORE, NS_STORES[ns_store])
+
+    def set_option(self, option: int, value: int):
+        self._check(_lib.signmuon_set_option(self._h, int(option), int(value)), "signmuon_set_option")
+
+    def get_option(self, option: int) -> int:
+        v = C.c_int()
+        self._check(_lib.signmuon_get_option(self._h, int(option), C.byref(v)), "signmuon_get_option")
+        return v.value
 
     def close(self):
         if getattr(self, "_h", None):
@@ -150,9 +171,11 @@ class Context:
         return n.value, ms.value
 
     def profile_work(self, kernel_class):
-        fl, by = C.c_double(), C.c_double()
-        self._check(_lib.signmuon_profile_work(self._h, kernel_class, C.byref(fl), C.byref(by)), "profile_work")
-        return fl.value, by.value
+        """(executed flop, dense flop, bytes) booked by the timed launches of a GEMM class."""
+        fl, fd, by = C.c_double(), C.c_double(), C.c_double()
+        self._check(_lib.signmuon_profile_work(self._h, kernel_class, C.byref(fl), C.byref(fd), C.byref(by)),
+                    "profile_work")
+        return fl.value, fd.value, by.value
 
 
 def kernel_name(kernel_class):

@@ -12,6 +12,7 @@
 #include <algorithm>
 
 #include "common.h"
+#include "../../include/signmuon_debug.h"
 
 struct ns_class {
   int rows = 0, cols = 0;  // logical shape
@@ -45,9 +46,9 @@ struct ns_plan {
   size_t total = 0;
 };
 
-void sm_plan_free(signmuon_ctx* ctx) {
-  delete ctx->plan;
-  ctx->plan = nullptr;
+void sm_plan_free(signmuon_ctx* ctx, int slot) {
+  delete ctx->ws[slot].plan;
+  ctx->ws[slot].plan = nullptr;
 }
 
 
@@ -58,15 +59,18 @@ T* at(signmuon_ctx* ctx, size_t off) {
   return reinterpret_cast<T*>(reinterpret_cast<unsigned char*>(ctx->arena) + off);
 }
 
-int get_plan(signmuon_ctx* ctx, int n, const int* rows, const int* cols, int M, int sign_fmt,
+// The plan of workspace `slot` for this set of shapes; makes that workspace's arena the current
+// one.  A new set of shapes replans: the arena is (re)allocated if it is too small and cleared.
+int get_plan(signmuon_ctx* ctx, int slot, int n, const int* rows, const int* cols, int M, int sign_fmt,
              ns_plan** out) {
-  ns_plan* pl = ctx->plan;
+  ns_plan* pl = ctx->ws[slot].plan;
   if (pl && pl->M == M && pl->sign_fmt == sign_fmt && (int)pl->rows.size() == n &&
       std::equal(rows, rows + n, pl->rows.begin()) && std::equal(cols, cols + n, pl->cols.begin())) {
+    ctx->arena = ctx->ws[slot].arena;
     *out = pl;
     return SM_OK;
   }
-  sm_plan_free(ctx);
+  sm_plan_free(ctx, slot);
   pl = new ns_plan();
   pl->rows.assign(rows, rows + n);
   pl->cols.assign(cols, cols + n);
@@ -135,14 +139,18 @@ int get_plan(signmuon_ctx* ctx, int n, const int* rows, const int* cols, int M, 
     pl->off_signs[i] = c.off_signs + (size_t)pl->index_in_class[i] * M * c.sign_stride;
   }
   pl->total = off;
-  int rc = sm_arena_reserve(ctx, pl->total);
+  int rc = sm_arena_reserve(ctx, slot, pl->total);
   if (rc != SM_OK) {
     delete pl;
     return rc;
   }
   // padding must read as zero
-  SM_HIP(ctx, hipMemsetAsync(ctx->arena, 0, pl->total, ctx->stream));
-  ctx->plan = pl;
+  hipError_t e = hipMemsetAsync(ctx->arena, 0, pl->total, ctx->stream);
+  if (e != hipSuccess) {
+    delete pl;
+    return sm_hip_fail(ctx, e, "hipMemsetAsync(workspace)");
+  }
+  ctx->ws[slot].plan = pl;
   *out = pl;
   return SM_OK;
 }
@@ -185,6 +193,7 @@ int launch_over_classes(signmuon_ctx* ctx, ns_plan* pl, const gemm_params& gp, i
         P[j].sign_out = nullptr;
         P[j].sign_stride = 0;
         P[j].sign_rows = P[j].sign_cols = P[j].sign_fmt = P[j].mate = 0;
+        P[j].mu = P[j].nu = P[j].ku = 0;
       }
       fill(pl->classes[c0 + i], P);
       // problems of one class given together share operands: deal their tiles item by item
@@ -209,6 +218,8 @@ void gram_of_y(ns_class& cl, sm_gemm_prob& P, const bf16_t* y, bf16_t* c, int ba
   P.ldc = cl.s;
   P.layout = cl.wide ? 0 : 3;
   P.batch = batch;
+  P.mu = P.nu = std::min(cl.rows, cl.cols);
+  P.ku = std::max(cl.rows, cl.cols);
 }
 
 // Y'[rp][cp] = S Y (rows <= cols; second operand stored [K][N]) or Y S, S symmetric s x s.
@@ -237,6 +248,9 @@ void apply_to_y(signmuon_ctx* ctx, ns_class& cl, sm_gemm_prob& P, const bf16_t* 
   P.ldc = cl.cp;
   P.K = cl.s;
   P.batch = batch;
+  P.mu = cl.rows;
+  P.nu = cl.cols;
+  P.ku = std::min(cl.rows, cl.cols);
   if (cl.wide) {
     P.A = sm;
     P.B = y;
@@ -266,6 +280,7 @@ void small_product(ns_class& cl, sm_gemm_prob& P, const bf16_t* a, const bf16_t*
   P.lda = P.ldb = P.ldc = cl.s;
   P.layout = 0;
   P.batch = batch;
+  P.mu = P.nu = P.ku = std::min(cl.rows, cl.cols);
 }
 
 // Step-by-step form of Alg. PolarNS: per step one Gram launch (Bm = a I + b G [+ c G^2], G the
@@ -362,12 +377,8 @@ int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const
   if (b == 0.f) return SM_EINVAL;  // run_ns routes b == 0 to the step-by-step form
   // The s x s matrices between the Gram and the apply are symmetric: only their 256 x 256 blocks on and
   // above the diagonal are written, and a product reads the other blocks as transposes of those
-  // (a third fewer bytes to and from memory).  SIGNMUON_NS_STORE=full writes and reads whole matrices.
-  static const bool full_store = [] {
-    const char* e = getenv("SIGNMUON_NS_STORE");
-    return e && strcmp(e, "full") == 0;
-  }();
-  const int ss = full_store ? 0 : 3;
+  // (a third fewer bytes to and from memory).  SM_NS_STORE_FULL writes and reads whole matrices.
+  const int ss = (ctx->opt[SM_OPT_NS_STORE] == SM_NS_STORE_FULL) ? 0 : 3;
   int done = 0;
   while (done < steps) {
     const int kk = std::min(SM_NS_SEGMENT, steps - done);
@@ -548,18 +559,13 @@ int run_ns_recurrence(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const
 // Runs `steps` Newton-Schulz steps on every class and returns the buffer index of the result.
 // The recurrence serves the cubic with |a| <= 1.5 (the paper's a = 3/2: growth of rounding noise
 // bounded by a^(2 (SM_NS_SEGMENT - 1)) < 26); other coefficients take the step-by-step form.
-// SIGNMUON_NS_PATH=stepwise forces the latter (for comparisons).
+// Option SM_OPT_NS_PATH forces the latter (SM_NS_PATH_STEPWISE) or the recurrence one step at a
+// time (SM_NS_PATH_SINGLE: three products per step), for comparisons.
 // signs (optional): the last apply also emits the packed signs of the classes marked fuse_signs.
 int run_ns(signmuon_ctx* ctx, ns_plan* pl, int mult, int steps, const float* coeffs, bool use_scale, int* cur_io,
            const ns_sign_req* signs = nullptr) {
-  static const bool force_stepwise = [] {
-    const char* e = getenv("SIGNMUON_NS_PATH");
-    return e && strcmp(e, "stepwise") == 0;
-  }();
-  static const bool force_single = [] {  // the recurrence one step at a time (3 products per step)
-    const char* e = getenv("SIGNMUON_NS_PATH");
-    return e && strcmp(e, "single") == 0;
-  }();
+  const bool force_stepwise = ctx->opt[SM_OPT_NS_PATH] == SM_NS_PATH_STEPWISE;
+  const bool force_single = ctx->opt[SM_OPT_NS_PATH] == SM_NS_PATH_SINGLE;
   if (!force_stepwise && coeffs[2] == 0.f && coeffs[1] != 0.f && fabsf(coeffs[0]) <= 1.5f && steps >= 2)
     return run_ns_recurrence(ctx, pl, mult, steps, coeffs, use_scale, cur_io, signs, !force_single);
   return run_ns_stepwise(ctx, pl, mult, steps, coeffs, use_scale, cur_io, signs);
@@ -620,36 +626,46 @@ int class_inv_sigma(signmuon_ctx* ctx, ns_plan* pl, int items, int mode, float e
   return sm_launch_sigma_group(ctx, d.data(), (int)d.size(), eps);
 }
 
+// Zeroes the padding of the first `items` matrices per block-count unit of buffer `buf` of every padded class:
+// items_per_class(cl) matrices starting at the buffer's base.
+template <typename F>
+int clear_padding(signmuon_ctx* ctx, ns_plan* pl, int buf, F items_per_class) {
+  std::vector<sm_pad_desc> d;
+  for (auto& cl : pl->classes) {
+    if (cl.rp == cl.rows && cl.cp == cl.cols) continue;
+    sm_pad_desc D;
+    D.x = at<bf16_t>(ctx, cl.off_x[buf]);
+    D.stride = cl.mat;
+    D.rows = cl.rows;
+    D.cols = cl.cols;
+    D.rp = cl.rp;
+    D.cp = cl.cp;
+    D.items = items_per_class(cl);
+    D.blocks_per_item = D.block_begin = D.pad_ = 0;
+    d.push_back(D);
+  }
+  if (d.empty()) return SM_OK;
+  return sm_launch_pad_clear(ctx, d.data(), (int)d.size());
+}
+
 bool bad_coeffs(const float* c) { return !c || !isfinite(c[0]) || !isfinite(c[1]) || !isfinite(c[2]); }
 
 }  // namespace
 
 extern "C" {
 
-int signmuon_momentum(signmuon_ctx* ctx, float* mom, const float* grad, const float* w, int M, int rows, int cols,
-                      float beta, float weight_decay, void* x_bf16, float* sumsq) {
-  if (!ctx) return SM_EINVAL;
-  if (!mom || !grad || M < 1 || rows < 1 || cols < 1) return sm_fail(ctx, SM_EINVAL, "momentum: bad pointer or size");
-  if (weight_decay != 0.f && !w) return sm_fail(ctx, SM_EINVAL, "momentum: weight_decay != 0 needs w");
-  if (!(beta >= 0.f && beta < 1.f)) return sm_fail(ctx, SM_EINVAL, "momentum: beta must be in [0, 1)");
-  if (!sm_aligned(mom, 4) || !sm_aligned(grad, 4) || (x_bf16 && !sm_aligned(x_bf16, 2)))
-    return sm_fail(ctx, SM_EINVAL, "momentum: misaligned pointer");
+// a1 for one block; partial sums of squares (when sumsq is asked for) go to `partial_buf`, which holds
+// partial_cap bytes.
+static int momentum_one(signmuon_ctx* ctx, float* mom, const float* grad, const float* w, int M, int rows, int cols,
+                        float beta, float weight_decay, void* x_bf16, float* sumsq, float* partial_buf) {
   const long long d = (long long)rows * cols;
   const int chunks = (int)((d + SM_MOM_CHUNK - 1) / SM_MOM_CHUNK);
-  float* partial = nullptr;
-  if (sumsq) {
-    // the partial sums go to the start of the arena, which may hold a plan's matrices: drop the plan
-    sm_plan_free(ctx);
-    int rc = sm_arena_reserve(ctx, (size_t)M * chunks * 4);
-    if (rc != SM_OK) return rc;
-    partial = reinterpret_cast<float*>(ctx->arena);
-  }
   sm_mom_desc D;
   D.mom = mom;
   D.grad = grad;
   D.w = (weight_decay != 0.f) ? w : nullptr;
   D.x = reinterpret_cast<bf16_t*>(x_bf16);
-  D.partial = partial;
+  D.partial = sumsq ? partial_buf : nullptr;
   D.d = d;
   D.x_stride = d;
   D.cols = cols;
@@ -658,8 +674,36 @@ int signmuon_momentum(signmuon_ctx* ctx, float* mom, const float* grad, const fl
   D.block_begin = 0;
   int rc = sm_launch_momentum(ctx, &D, 1, M, beta, weight_decay);
   if (rc != SM_OK) return rc;
-  if (sumsq) return sm_launch_reduce_partials(ctx, partial, chunks, M, sumsq);
+  if (sumsq) return sm_launch_reduce_partials(ctx, partial_buf, chunks, M, sumsq);
   return SM_OK;
+}
+
+static int momentum_check(signmuon_ctx* ctx, float* mom, const float* grad, const float* w, int M, int rows, int cols,
+                          float beta, float weight_decay, void* x_bf16, float* sumsq) {
+  if (!mom || !grad || M < 1 || rows < 1 || cols < 1) return sm_fail(ctx, SM_EINVAL, "momentum: bad pointer or size");
+  if (weight_decay != 0.f && !w) return sm_fail(ctx, SM_EINVAL, "momentum: weight_decay != 0 needs w");
+  if (!(beta >= 0.f && beta < 1.f)) return sm_fail(ctx, SM_EINVAL, "momentum: beta must be in [0, 1)");
+  if (!sm_aligned(mom, 4) || !sm_aligned(grad, 4) || (w && !sm_aligned(w, 4)) || (x_bf16 && !sm_aligned(x_bf16, 2)) ||
+      (sumsq && !sm_aligned(sumsq, 4)))
+    return sm_fail(ctx, SM_EINVAL, "momentum: misaligned pointer");
+  const long long chunks = ((long long)rows * cols + SM_MOM_CHUNK - 1) / SM_MOM_CHUNK;
+  if (chunks * M > 0x7FFFFFFFLL) return sm_fail(ctx, SM_EUNSUPPORTED, "momentum: too many entries for one launch");
+  return SM_OK;
+}
+
+int signmuon_momentum(signmuon_ctx* ctx, float* mom, const float* grad, const float* w, int M, int rows, int cols,
+                      float beta, float weight_decay, void* x_bf16, float* sumsq) {
+  if (!ctx) return SM_EINVAL;
+  int rc = momentum_check(ctx, mom, grad, w, M, rows, cols, beta, weight_decay, x_bf16, sumsq);
+  if (rc != SM_OK) return rc;
+  if (sumsq) {
+    // per-chunk partial sums: the context's small scratch (not the step's workspace)
+    const long long chunks = ((long long)rows * cols + SM_MOM_CHUNK - 1) / SM_MOM_CHUNK;
+    rc = sm_aux_reserve(ctx, (size_t)M * chunks * 4);
+    if (rc != SM_OK) return rc;
+  }
+  return momentum_one(ctx, mom, grad, w, M, rows, cols, beta, weight_decay, x_bf16, sumsq,
+                      reinterpret_cast<float*>(ctx->aux));
 }
 
 int signmuon_polar_ns(signmuon_ctx* ctx, void* x, int dtype, int batch, int rows, int cols, const float* coeffs,
@@ -674,11 +718,14 @@ int signmuon_polar_ns(signmuon_ctx* ctx, void* x, int dtype, int batch, int rows
     return sm_fail(ctx, SM_EINVAL, "polar_ns: spectral scale needs v0 and power_iters >= 0");
   if (!(eps >= 0.f)) return sm_fail(ctx, SM_EINVAL, "polar_ns: eps must be >= 0");
   if (!sm_aligned(x, dtype == SM_F32 ? 4 : 2)) return sm_fail(ctx, SM_EINVAL, "polar_ns: misaligned x");
+  if (batch > 65535) return sm_fail(ctx, SM_EUNSUPPORTED, "polar_ns: batch > 65535");
   ns_plan* pl = nullptr;
-  int rc = get_plan(ctx, 1, &rows, &cols, batch, -1, &pl);
+  int rc = get_plan(ctx, SM_WS_NS, 1, &rows, &cols, batch, -1, &pl);
   if (rc != SM_OK) return rc;
   ns_class& cl = pl->classes[0];
   rc = sm_launch_copy_in(ctx, x, dtype, batch, rows, cols, at<bf16_t>(ctx, cl.off_x[0]), cl.cp, cl.mat);
+  if (rc != SM_OK) return rc;
+  rc = clear_padding(ctx, pl, 0, [&](ns_class&) { return batch; });
   if (rc != SM_OK) return rc;
   bool use_scale = false;
   if (scale == SM_SCALE_FRO) {
@@ -792,7 +839,8 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
       return sm_fail(ctx, SM_EINVAL, "step: counts_out needs 16-byte alignment");
   }
   ns_plan* pl = nullptr;
-  int rc = get_plan(ctx, n, s->rows, s->cols, M, s->sign_fmt, &pl);
+  if (M > 65535) return sm_fail(ctx, SM_EUNSUPPORTED, "step: M > 65535");
+  int rc = get_plan(ctx, SM_WS_STEP, n, s->rows, s->cols, M, s->sign_fmt, &pl);
   if (rc != SM_OK) return rc;
 
   // a1: momentum for every block and worker, with the bf16 working copy and the sums of squares
@@ -814,6 +862,10 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
     D.block_begin = 0;
   }
   rc = sm_launch_momentum(ctx, descs.data(), n, M, s->beta, s->weight_decay);
+  if (rc != SM_OK) return rc;
+  // the momentum kernel writes the logical entries of X only: restore the zero padding, which an
+  // earlier call with a non-finite matrix may have turned into NaN
+  rc = clear_padding(ctx, pl, 0, [&](ns_class& cl) { return cl.count * M; });
   if (rc != SM_OK) return rc;
 
   // a2: sigma per (block, worker)
@@ -927,6 +979,9 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
     }
   }
   if (Kp == 0 && !op_norm) return SM_OK;
+  // the voted matrices took over slots that held some workers' matrices before the vote: zero their padding
+  rc = clear_padding(ctx, pl, cur ^ 1, [&](ns_class& cl) { return cl.count; });
+  if (rc != SM_OK) return rc;
 
   // a7: local polar step on the voted sign matrices (one per block), or their operator norm for
   // the normalized-sign update (worker 0's start vector serves the voted matrix of each block)

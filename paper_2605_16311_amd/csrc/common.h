@@ -27,19 +27,31 @@ struct signmuon_ctx {
   int device = 0;
   std::string last_error;
 
-  // one growable device arena; sub-allocated by the NS plan
+  // Workspaces: one growable device arena each, sub-allocated by a cached Newton-Schulz plan
+  // (shape classes + offsets).  Slot SM_WS_STEP serves signmuon_step, SM_WS_NS signmuon_polar_ns,
+  // so that calls of the two interleave without replanning.  `arena` is the arena of the slot
+  // in use by the running call.
+  struct workspace {
+    void* arena = nullptr;
+    size_t bytes = 0;
+    struct ns_plan* plan = nullptr;
+  } ws[2];
   void* arena = nullptr;
-  size_t arena_bytes = 0;
+  // small scratch of the standalone entry points (partial sums of signmuon_momentum)
+  void* aux = nullptr;
+  size_t aux_bytes = 0;
 
-  // cached NS plan (shape classes + workspace offsets)
-  struct ns_plan* plan = nullptr;
+  // tuning switches (signmuon_set_option)
+  int opt[SM_OPT_COUNT] = {};
+  int n_cu = 256;  // compute units of the device
 
   // timing taps
   unsigned profiling = 0;  // bit k set: launches of kernel class k are bracketed with events
   std::vector<sm_event_pair> ev_pool;        // every pair ever created
   size_t ev_used = 0;                        // pairs handed out since the last reset
   std::vector<std::pair<int, size_t>> ev_log;  // (kernel class, pool index)
-  double work_flop[SM_K_COUNT] = {};         // matrix-product flops booked by timed GEMM launches
+  double work_flop[SM_K_COUNT] = {};         // flops of the output tiles that timed GEMM launches compute (logical sizes)
+  double work_dense[SM_K_COUNT] = {};        // 2 M N K of the same products as written
   double work_bytes[SM_K_COUNT] = {};        // their operand + result bytes
 };
 
@@ -61,8 +73,12 @@ struct sm_launch_scope {
   ~sm_launch_scope();
 };
 
-// Ensures the arena holds at least `bytes`; contents are lost when it grows.
-int sm_arena_reserve(signmuon_ctx* ctx, size_t bytes);
+constexpr int SM_WS_STEP = 0, SM_WS_NS = 1;
+// Ensures the arena of workspace `slot` holds at least `bytes` and makes it the current arena;
+// contents (and the slot's plan) are lost when it grows.
+int sm_arena_reserve(signmuon_ctx* ctx, int slot, size_t bytes);
+// Ensures the auxiliary scratch holds at least `bytes`.
+int sm_aux_reserve(signmuon_ctx* ctx, size_t bytes);
 
 static inline int64_t sm_round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 static inline bool sm_aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -173,6 +189,19 @@ int sm_launch_copy_in(signmuon_ctx* ctx, const void* src, int dtype, int batch, 
 // dst[b][rows][cols] (f32 or bf16) <- scale[b] * src[b][rows][ld]; scale may be null
 int sm_launch_copy_out(signmuon_ctx* ctx, const bf16_t* src, int ld, long long src_stride, int batch, int rows,
                        int cols, void* dst, int dtype, const float* scale);
+// Writes zeros over the padding (columns cols..cp, rows rows..rp) of `items` matrices [rp][cp], `stride`
+// elements apart: the working layout relies on padding that reads as zero, and a non-finite input would
+// otherwise leave NaN there for every later call (0 * NaN in a product's padded rows).
+struct sm_pad_desc {
+  bf16_t* x;
+  long long stride;
+  int rows, cols, rp, cp;
+  int items;
+  int blocks_per_item, block_begin;  // filled by the launcher
+  int pad_;
+};
+constexpr int SM_PAD_MAX_GROUP = 64;
+int sm_launch_pad_clear(signmuon_ctx* ctx, const sm_pad_desc* descs, int n);
 // sumsq[b] = sum of squares of x[b][0..n) (f32 or bf16; two stages, fixed order);
 // scratch: batch * ceil(n / SM_MOM_CHUNK) floats
 int sm_launch_sumsq(signmuon_ctx* ctx, const void* x, int dtype, long long n_per_batch, int batch, float* scratch,
@@ -211,6 +240,8 @@ struct sm_gemm_prob {
   // item right after this problem's (item b of this one, item b of the mate, item b + 1, ...), so
   // that operands the two share are read from HBM once; 0 = none.  The mate owns no tiles itself.
   int mate;
+  // logical (unpadded) M, N, K for the work accounting of the timing taps; 0 = as M, N, K
+  int mu, nu, ku;
 };
 constexpr int SM_GEMM_MAX_PROB = 24;
 struct sm_gemm_args {

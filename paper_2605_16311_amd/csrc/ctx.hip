@@ -3,6 +3,8 @@
 
 #include <stdio.h>
 
+#include <algorithm>
+
 int sm_fail(signmuon_ctx* ctx, int code, const std::string& msg) {
   if (ctx) ctx->last_error = msg;
   return code;
@@ -35,31 +37,54 @@ sm_launch_scope::~sm_launch_scope() {
   ctx->ev_log.emplace_back(klass, (size_t)idx);
 }
 
-void sm_plan_free(signmuon_ctx* ctx);  // api.hip
+void sm_plan_free(signmuon_ctx* ctx, int slot);  // api.hip
 
-int sm_arena_reserve(signmuon_ctx* ctx, size_t bytes) {
-  if (bytes <= ctx->arena_bytes) return SM_OK;
-  sm_plan_free(ctx);  // a plan's zero padding does not survive a new allocation
-  if (ctx->arena) {
-    SM_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    SM_HIP(ctx, hipFree(ctx->arena));
-    ctx->arena = nullptr;
-    ctx->arena_bytes = 0;
+int sm_arena_reserve(signmuon_ctx* ctx, int slot, size_t bytes) {
+  signmuon_ctx::workspace& w = ctx->ws[slot];
+  if (bytes > w.bytes) {
+    sm_plan_free(ctx, slot);  // a plan's zero padding does not survive a new allocation
+    if (w.arena) {
+      SM_HIP(ctx, hipStreamSynchronize(ctx->stream));
+      SM_HIP(ctx, hipFree(w.arena));
+      w.arena = nullptr;
+      w.bytes = 0;
+    }
+    void* p = nullptr;
+    hipError_t e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      return sm_fail(ctx, SM_ENOMEM, "workspace allocation of " + std::to_string(bytes) + " bytes failed");
+    }
+    w.arena = p;
+    w.bytes = bytes;
   }
+  ctx->arena = w.arena;
+  return SM_OK;
+}
+
+int sm_aux_reserve(signmuon_ctx* ctx, size_t bytes) {
+  if (bytes <= ctx->aux_bytes) return SM_OK;
+  if (ctx->aux) {
+    SM_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    SM_HIP(ctx, hipFree(ctx->aux));
+    ctx->aux = nullptr;
+    ctx->aux_bytes = 0;
+  }
+  bytes = std::max<size_t>(bytes, 1u << 20);
   void* p = nullptr;
   hipError_t e = hipMalloc(&p, bytes);
   if (e != hipSuccess) {
     (void)hipGetLastError();
-    return sm_fail(ctx, SM_ENOMEM, "workspace allocation of " + std::to_string(bytes) + " bytes failed");
+    return sm_fail(ctx, SM_ENOMEM, "scratch allocation of " + std::to_string(bytes) + " bytes failed");
   }
-  ctx->arena = p;
-  ctx->arena_bytes = bytes;
+  ctx->aux = p;
+  ctx->aux_bytes = bytes;
   return SM_OK;
 }
 
 extern "C" {
 
-int signmuon_create(signmuon_ctx** out, void* hip_stream) {
+int signmuon_create(signmuon_ctx** out, void* hip_stream, size_t workspace_bytes_hint) {
   if (!out) return SM_EINVAL;
   *out = nullptr;
   int dev = 0;
@@ -72,6 +97,14 @@ int signmuon_create(signmuon_ctx** out, void* hip_stream) {
   signmuon_ctx* c = new signmuon_ctx();
   c->stream = (hipStream_t)hip_stream;
   c->device = dev;
+  c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  if (workspace_bytes_hint) {
+    const int rc = sm_arena_reserve(c, SM_WS_STEP, workspace_bytes_hint);
+    if (rc != SM_OK) {
+      delete c;
+      return rc;
+    }
+  }
   *out = c;
   return SM_OK;
 }
@@ -79,13 +112,36 @@ int signmuon_create(signmuon_ctx** out, void* hip_stream) {
 int signmuon_destroy(signmuon_ctx* ctx) {
   if (!ctx) return SM_EINVAL;
   (void)hipStreamSynchronize(ctx->stream);
-  sm_plan_free(ctx);
-  if (ctx->arena) (void)hipFree(ctx->arena);
+  for (int slot = 0; slot < 2; ++slot) {
+    sm_plan_free(ctx, slot);
+    if (ctx->ws[slot].arena) (void)hipFree(ctx->ws[slot].arena);
+  }
+  if (ctx->aux) (void)hipFree(ctx->aux);
   for (auto& p : ctx->ev_pool) {
     (void)hipEventDestroy(p.a);
     (void)hipEventDestroy(p.b);
   }
   delete ctx;
+  return SM_OK;
+}
+
+int signmuon_set_option(signmuon_ctx* ctx, int option, int value) {
+  if (!ctx) return SM_EINVAL;
+  bool ok = false;
+  switch (option) {
+    case SM_OPT_GEMM_TILE: ok = (value == 0 || value == 128 || value == 256); break;
+    case SM_OPT_NS_PATH: ok = (value >= SM_NS_PATH_PAIRS && value <= SM_NS_PATH_STEPWISE); break;
+    case SM_OPT_NS_STORE: ok = (value == SM_NS_STORE_UPPER || value == SM_NS_STORE_FULL); break;
+    default: break;
+  }
+  if (!ok) return sm_fail(ctx, SM_EINVAL, "set_option: unknown option or value");
+  ctx->opt[option] = value;
+  return SM_OK;
+}
+
+int signmuon_get_option(const signmuon_ctx* ctx, int option, int* value) {
+  if (!ctx || !value || option < 0 || option >= SM_OPT_COUNT) return SM_EINVAL;
+  *value = ctx->opt[option];
   return SM_OK;
 }
 
@@ -102,7 +158,9 @@ const char* signmuon_strerror(int status) {
 
 const char* signmuon_last_error(const signmuon_ctx* ctx) { return ctx ? ctx->last_error.c_str() : ""; }
 
-size_t signmuon_workspace_bytes(const signmuon_ctx* ctx) { return ctx ? ctx->arena_bytes : 0; }
+size_t signmuon_workspace_bytes(const signmuon_ctx* ctx) {
+  return ctx ? ctx->ws[0].bytes + ctx->ws[1].bytes + ctx->aux_bytes : 0;
+}
 
 int signmuon_profile_enable(signmuon_ctx* ctx, unsigned class_mask) {
   if (!ctx) return SM_EINVAL;
@@ -115,13 +173,15 @@ int signmuon_profile_reset(signmuon_ctx* ctx) {
   SM_HIP(ctx, hipStreamSynchronize(ctx->stream));
   ctx->ev_used = 0;
   ctx->ev_log.clear();
-  for (int k = 0; k < SM_K_COUNT; ++k) ctx->work_flop[k] = ctx->work_bytes[k] = 0.0;
+  for (int k = 0; k < SM_K_COUNT; ++k) ctx->work_flop[k] = ctx->work_dense[k] = ctx->work_bytes[k] = 0.0;
   return SM_OK;
 }
 
-int signmuon_profile_work(signmuon_ctx* ctx, int kernel_class, double* flop, double* bytes) {
+int signmuon_profile_work(signmuon_ctx* ctx, int kernel_class, double* flop_executed, double* flop_dense,
+                          double* bytes) {
   if (!ctx || kernel_class < 0 || kernel_class >= SM_K_COUNT) return SM_EINVAL;
-  if (flop) *flop = ctx->work_flop[kernel_class];
+  if (flop_executed) *flop_executed = ctx->work_flop[kernel_class];
+  if (flop_dense) *flop_dense = ctx->work_dense[kernel_class];
   if (bytes) *bytes = ctx->work_bytes[kernel_class];
   return SM_OK;
 }

@@ -3,6 +3,8 @@
 // the Frobenius scale of Alg. PolarNS.
 #include "common.h"
 
+#include <algorithm>
+
 namespace {
 
 constexpr int TPB = 256;
@@ -64,7 +66,63 @@ __global__ void __launch_bounds__(TPB) sm_sumsq_kernel(const void* __restrict__ 
   if (threadIdx.x == 0) partial[(long long)b * chunks + ch] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
+struct pad_args {
+  int n;
+  int pad_;
+  sm_pad_desc d[SM_PAD_MAX_GROUP];
+};
+
+// Zero padding of the working layout: thread = one padding element of one matrix, first the strip to the
+// right of the logical columns (row by row), then the rows below the logical ones.
+__global__ void __launch_bounds__(TPB) sm_pad_clear_kernel(const pad_args a) {
+  int di = 0;
+  while (di + 1 < a.n && (int)blockIdx.x >= a.d[di + 1].block_begin) ++di;
+  const sm_pad_desc& D = a.d[di];
+  const int local = blockIdx.x - D.block_begin;
+  const int item = local / D.blocks_per_item;
+  const long long e = (long long)(local - item * D.blocks_per_item) * TPB + threadIdx.x;
+  const int pc = D.cp - D.cols;
+  const long long right = (long long)D.rows * pc, total = right + (long long)(D.rp - D.rows) * D.cp;
+  if (e >= total) return;
+  long long r, c;
+  if (e < right) {
+    r = e / pc;
+    c = D.cols + e % pc;
+  } else {
+    r = D.rows + (e - right) / D.cp;
+    c = (e - right) % D.cp;
+  }
+  D.x[(long long)item * D.stride + r * D.cp + c] = (bf16_t)0.0f;
+}
+
 }  // namespace
+
+int sm_launch_pad_clear(signmuon_ctx* ctx, const sm_pad_desc* descs, int n) {
+  int done = 0;
+  while (done < n) {
+    const int g = std::min(n - done, SM_PAD_MAX_GROUP);
+    pad_args a;
+    a.n = g;
+    a.pad_ = 0;
+    long long blocks = 0;
+    for (int i = 0; i < g; ++i) {
+      sm_pad_desc& D = a.d[i];
+      D = descs[done + i];
+      const long long total = (long long)D.rows * (D.cp - D.cols) + (long long)(D.rp - D.rows) * D.cp;
+      D.blocks_per_item = (int)((total + TPB - 1) / TPB);
+      D.block_begin = (int)blocks;
+      blocks += (long long)D.blocks_per_item * D.items;
+    }
+    if (blocks > 0x7FFFFFFFLL) return sm_fail(ctx, SM_EUNSUPPORTED, "padding clear: too many elements for one launch");
+    if (blocks > 0) {
+      sm_launch_scope sc(ctx, SM_K_OTHER);
+      hipLaunchKernelGGL(sm_pad_clear_kernel, dim3((unsigned)blocks), dim3(TPB), 0, ctx->stream, a);
+    }
+    SM_HIP(ctx, hipGetLastError());
+    done += g;
+  }
+  return SM_OK;
+}
 
 int sm_launch_copy_in(signmuon_ctx* ctx, const void* src, int dtype, int batch, int rows, int cols, bf16_t* dst,
                       int ld, long long dst_stride) {

@@ -49,6 +49,7 @@
 // operand form (MN for the transposed blocks, KC for the stored ones) at block boundaries.
 // A third fewer bytes go to and come from memory, which is what bounds those products.
 #include "common.h"
+#include "../../include/signmuon_debug.h"
 #include <type_traits>
 
 namespace sm_gemm {
@@ -780,6 +781,7 @@ extern "C" int signmuon_debug_tile_ranges(int n_prob, const int* M, const int* N
     a.p[i].K = K[i];
     a.p[i].batch = batch[i];
     a.p[i].mate = mate ? mate[i] : 0;
+    a.p[i].mu = a.p[i].nu = a.p[i].ku = 0;
   }
   fill_tiles(a, sym != 0, ts);
   for (int x = 0; x < 9; ++x) xcd_begin[x] = a.xcd_begin[x];
@@ -824,11 +826,7 @@ int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, bool sym, int klass) {
     if (a_ext * 2 >= 0x7FFFFFFFLL || b_ext * 2 >= 0x7FFFFFFFLL)
       return sm_fail(ctx, SM_EUNSUPPORTED, "internal: GEMM operand larger than 2 GiB");
   }
-  static const int env_tile = [] {
-    const char* e = getenv("SIGNMUON_GEMM_TILE");
-    return e ? atoi(e) : 0;
-  }();
-  int ts = env_tile;
+  int ts = ctx->opt[SM_OPT_GEMM_TILE];
   if (ts != 128 && ts != 256) {
     // 256 x 256 tiles once there are enough of them to keep 256 CUs busy for several rounds
     fill_tiles(args, gram, 256);
@@ -837,19 +835,21 @@ int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, bool sym, int klass) {
   const int most = fill_tiles(args, gram, ts);
   if (args.total_tiles == 0) return SM_OK;
   // persistent grid: one workgroup per CU (two for the small tile), a multiple of 8, never more than tiles
-  static const int n_cu = [] {
-    int dev = 0, n = 256;
-    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
-    return n;
-  }();
-  int wgs = n_cu * (ts == 128 ? 2 : 1);
-  wgs = std::min(wgs / 8, most) * 8;
+  int wgs = ctx->n_cu * (ts == 128 ? 2 : 1);
+  wgs = std::max(1, std::min(wgs / 8, most)) * 8;
   const dim3 grid(wgs), block(NTH);
   if ((ctx->profiling >> klass) & 1u) {
     for (int i = 0; i < args.n_prob; ++i) {
       const sm_gemm_prob& P = args.p[i];
       const double mnk = (double)P.M * P.N * P.K * P.batch;
-      ctx->work_flop[klass] += 2.0 * mnk;
+      ctx->work_dense[klass] += 2.0 * mnk;
+      // executed: the tiles this launch computes, each clipped to the logical extent of the product
+      const int mu = P.mu ? P.mu : P.M, nu = P.nu ? P.nu : P.N, ku = P.ku ? P.ku : P.K;
+      double area = 0.0;
+      for (int tn = 0; tn < P.tiles_n; ++tn)
+        for (int tm = 0; tm < (gram ? tn + 1 : P.tiles_m); ++tm)
+          area += (double)std::max(0, std::min(ts, mu - tm * ts)) * std::max(0, std::min(ts, nu - tn * ts));
+      ctx->work_flop[klass] += 2.0 * area * ku * P.batch;
       const bool same = (P.A == P.B);
       // upper-block storage: the share of an s x s matrix that lies in its 256 x 256 blocks on and above the diagonal
       auto upper_share = [](int s) {

@@ -1,19 +1,41 @@
-"""The C-ABI library loads and exports every function include/signmuon.h declares (no GPU needed)."""
+"""The C-ABI library loads, exports every function the headers under include/ declare, and exports no
+signmuon_* symbol that they do not declare (no GPU needed)."""
 import ctypes
 import os
 import re
+import subprocess
 
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "signmuon.h")
+DEBUG_HEADER = os.path.join(ROOT, "include", "signmuon_debug.h")
 LIB = os.path.join(ROOT, "paper_2605_16311_amd", "libsignmuon.so")
 
 
-def declared_functions():
-    text = open(HEADER).read()
+def declared_functions(header=HEADER):
+    text = open(header).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(signmuon_[a-z0-9_]+)\s*\(", text)))
+
+
+def exported_symbols():
+    out = subprocess.run(["nm", "-D", "--defined-only", LIB], check=True, capture_output=True, text=True).stdout
+    syms = set()
+    for line in out.splitlines():
+        parts = line.split()
+        if len(parts) >= 3 and parts[1] in "TtWw" and parts[2].startswith("signmuon_"):
+            syms.add(parts[2])
+    return sorted(syms)
+
+
+def test_every_exported_symbol_is_declared_in_a_header():
+    if not os.path.exists(LIB):
+        pytest.fail(f"{LIB} missing: run __graft_entry__.build() first")
+    declared = set(declared_functions(HEADER)) | set(declared_functions(DEBUG_HEADER))
+    exported = exported_symbols()
+    assert exported, "nm found no signmuon_* symbols"
+    assert set(exported) == declared, (sorted(set(exported) - declared), sorted(declared - set(exported)))
 
 
 def test_header_declares_the_five_path_calls():
@@ -28,7 +50,7 @@ def test_library_exports_every_declared_symbol():
         pytest.fail(f"{LIB} missing: run __graft_entry__.build() first")
     import torch  # noqa: F401  (loads the HIP runtime the library links against)
     lib = ctypes.CDLL(LIB)
-    for n in declared_functions():
+    for n in declared_functions() + declared_functions(DEBUG_HEADER):
         assert hasattr(lib, n), n
 
 

@@ -32,6 +32,30 @@ def ctx(P):
     c.close()
 
 
+# Settings of the context's tuning switches (GEMM tile, grouping of the K steps, storage of the s x s
+# matrices) under which the Newton-Schulz and whole-step cases are repeated; "auto" is what a caller gets.
+VARIANTS = {
+    "auto": dict(),
+    "t128-pairs-upper": dict(gemm_tile=128),
+    "t256-pairs-upper": dict(gemm_tile=256),
+    "t128-pairs-full": dict(gemm_tile=128, ns_store="full"),
+    "t256-pairs-full": dict(gemm_tile=256, ns_store="full"),
+    "t128-single-upper": dict(gemm_tile=128, ns_path="single"),
+    "t256-single-upper": dict(gemm_tile=256, ns_path="single"),
+    "t256-single-full": dict(gemm_tile=256, ns_path="single", ns_store="full"),
+    "t128-stepwise": dict(gemm_tile=128, ns_path="stepwise"),
+    "t256-stepwise": dict(gemm_tile=256, ns_path="stepwise"),
+}
+
+
+@pytest.fixture(scope="module", params=list(VARIANTS))
+def vctx(P, request):
+    c = P.Context(**VARIANTS[request.param])
+    yield c
+    torch.cuda.synchronize()
+    c.close()
+
+
 def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
@@ -301,7 +325,8 @@ NS_CASES = [
 
 @pytest.mark.parametrize("batch,r,c,steps,scale,coeffs", NS_CASES)
 @pytest.mark.parametrize("dt", ["bf16", "f32"])
-def test_polar_ns_against_fp32_oracle(P, ctx, batch, r, c, steps, scale, coeffs, dt):
+def test_polar_ns_against_fp32_oracle(P, vctx, batch, r, c, steps, scale, coeffs, dt):
+    ctx = vctx
     x = wl.normal((batch, r, c), stream=26, block=r, worker=c)
     if scale == "none":
         x = x / (1.05 * np.linalg.norm(x, ord=2, axis=(1, 2), keepdims=True)).astype(np.float32)
@@ -387,8 +412,9 @@ def run_step_case(P, ctx, shapes, M, *, sign_fmt, Kp, K=5, scale="fro", wd=0.0, 
     return plan
 
 
-def test_step_single256(P, ctx):
+def test_step_single256(P, vctx):
     """256x256, M=4, N(0,1) gradients from zero momentum, 5 NS steps, 1-bit, no local polar."""
+    ctx = vctx
     cfg = wl.WORKLOADS["single256"]
     shapes, M = cfg["shapes"], cfg["M"]
     G = [wl.worker_grads("single256", 0, 256, 256)]
@@ -397,7 +423,8 @@ def test_step_single256(P, ctx):
 
 @pytest.mark.parametrize("sign_fmt", ["1bit", "int8"])
 @pytest.mark.parametrize("Kp", [0, 3])
-def test_step_mixed_set(P, ctx, sign_fmt, Kp):
+def test_step_mixed_set(P, vctx, sign_fmt, Kp):
+    ctx = vctx
     # (200, 160) and (96, 224): signs packed by the apply GEMM with zero padding in both dimensions;
     # (100, 72): rows that do not pack into whole words (separate sign-pack launch)
     shapes = [(64, 192), (192, 64), (64, 192), (128, 128), (100, 72), (64, 192), (200, 160), (96, 224)]
@@ -405,14 +432,16 @@ def test_step_mixed_set(P, ctx, sign_fmt, Kp):
 
 
 @pytest.mark.parametrize("special", [False, True])
-def test_step_signs_written_by_the_apply_alone(P, ctx, special):
+def test_step_signs_written_by_the_apply_alone(P, vctx, special):
     """Without a u_out tap the last apply writes only the packed signs (U is never stored; the bits come
     straight from the accumulators).  The same step with all taps (checked against the oracle by the cases
     above; there the signs are taken from the stored bf16 U) must give the same signs, counts and W.
     special: a column of entries near the bottom of the fp32 range (its outputs fall among the
     denormals, negative ones included), a NaN (the whole matrix turns NaN: all signs -1) and a zero matrix."""
-    # (64, 100) cannot be packed by the GEMM; (200, 160) is packed with padding in both dimensions
-    shapes, M = [(128, 256), (256, 128), (192, 192), (64, 100), (200, 160)], 3
+    # (64, 100) cannot be packed by the GEMM; (200, 160) is packed with padding in both dimensions;
+    # (320, 576) and (576, 320) span two tiles of 256 each way with a ragged second tile
+    ctx = vctx
+    shapes, M = [(128, 256), (256, 128), (192, 192), (64, 100), (200, 160), (320, 576), (576, 320)], 3
     outs = []
     for tapped in (True, False):
         w = [dev(wl.weights(r, c, block=i)) for i, (r, c) in enumerate(shapes)]
@@ -423,6 +452,9 @@ def test_step_signs_written_by_the_apply_alone(P, ctx, special):
             g_host[0][:, :, 5] = sgn * np.float32(3e-37)
             g_host[1][0, 7, 9] = np.float32("nan")
             g_host[2][1] = 0.0
+            sgn = np.where(wl.normal((M, 320), stream=35) >= 0, 1.0, -1.0).astype(np.float32)
+            g_host[5][:, :, 300] = sgn * np.float32(3e-37)          # a column in the second 256-tile
+            g_host[6][2, 400, 17] = np.float32("nan")
         grad = [dev(g) for g in g_host]
         d = [r * c for r, c in shapes]
         signs = [torch.zeros((M, O.packed_stride_bytes(x)), dtype=torch.uint8, device="cuda") for x in d]
@@ -512,8 +544,45 @@ def test_step_with_normalized_sign_update(P, ctx):
                                         update_rsqrt_mn="op_norm", local_polar_steps=2))
 
 
-def test_step_spectral(P, ctx):
-    run_step_case(P, ctx, [(128, 256), (256, 128)], 2, sign_fmt="1bit", Kp=2, scale="spectral")
+def test_step_spectral(P, vctx):
+    run_step_case(P, vctx, [(128, 256), (256, 128)], 2, sign_fmt="1bit", Kp=2, scale="spectral")
+
+
+def test_nan_worker_on_a_padded_shape_does_not_leak_into_other_blocks(P):
+    """A NaN in one worker's gradient turns that worker's whole matrix NaN (every sign -1), zero padding of its
+    slots in the working layout included.  After the vote those slots hold other blocks' voted matrices, so
+    the padding is cleared again: the blocks without a NaN worker must come out exactly as in a run where
+    the NaN is replaced by an ordinary number.  200 x 160 pads both dimensions; K = 7 makes both working
+    buffers carry apply outputs; the local polar step reads the voted matrices with their padding."""
+    shapes, M = [(200, 160)] * 3 + [(136, 200)] * 2, 3
+
+    def run(ctx, poisoned):
+        G = [wl.normal((M, r, c), stream=36, block=i) for i, (r, c) in enumerate(shapes)]
+        if poisoned:
+            G[0][1, 3, 4] = np.float32("nan")
+            G[3][2, 100, 150] = np.float32("inf")
+        w = [dev(wl.weights(r, c, block=i, stream=36)) for i, (r, c) in enumerate(shapes)]
+        mom = [torch.zeros((M, r, c), device="cuda") for r, c in shapes]
+        d_out = [torch.zeros((r, c), dtype=torch.bfloat16, device="cuda") for r, c in shapes]
+        plan = P.StepPlan(w, mom, [dev(g) for g in G], beta=0.9, lr=1e-2, ns_steps=7, local_polar_steps=3, d_out=d_out)
+        P.signmuon_step(ctx, plan)
+        torch.cuda.synchronize()
+        return [t.cpu().numpy() for t in w], [bf16_host(t) for t in d_out]
+
+    c0 = P.Context()
+    w_ref, d_ref = run(c0, False)
+    c0.close()
+    c1 = P.Context()
+    w_bad, d_bad = run(c1, True)
+    w_after, d_after = run(c1, False)          # the same context, after it has seen the NaN
+    c1.close()
+    for i in range(len(shapes)):
+        assert np.isfinite(w_ref[i]).all() and np.isfinite(d_ref[i]).all()
+        assert np.array_equal(w_after[i], w_ref[i]) and np.array_equal(d_after[i], d_ref[i]), f"block {i} after the NaN"
+    for i in (1, 2, 4):                        # blocks whose workers are all finite
+        assert np.array_equal(w_bad[i], w_ref[i]) and np.array_equal(d_bad[i], d_ref[i]), f"block {i} beside the NaN"
+    for i in (0, 3):                           # the vote tolerates the non-finite worker (its signs are all -1)
+        assert np.isfinite(w_bad[i]).all() and np.isfinite(d_bad[i]).all()
 
 
 def test_step_signsgd_limit_and_zero_gradients(P, ctx):
