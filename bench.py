@@ -142,6 +142,10 @@ def run_workload(name, steps, warmup, torch, P, B, scale=None):
     ms_pack = per_class[P.kernel_name(B.SM_K_SIGN_PACK)]["ms_per_step"]
     ms_vote = per_class[P.kernel_name(B.SM_K_VOTE)]["ms_per_step"]
     ms_mom = per_class[P.kernel_name(B.SM_K_MOMENTUM)]["ms_per_step"]
+    # Alg. PowerIter with P = 2: 2 P + 1 products with X, i.e. 2 P + 1 passes over the bf16 X of every worker before
+    # the vote and over the voted matrices after it (algorithmic bytes; the fused pass reads X P + 1 times)
+    ms_pi = per_class[P.kernel_name(B.SM_K_POWER_ITER)]["ms_per_step"]
+    pi_bytes = 5.0 * 2.0 * d_total * (M + (1 if Kp else 0)) if scale == "spectral" else 0.0
     res = {
         "workload": name, "M": M, "n_blocks": len(shapes), "entries": d_total, "ns_steps": K,
         "local_polar_steps": Kp, "scale": scale,
@@ -159,6 +163,10 @@ def run_workload(name, steps, warmup, torch, P, B, scale=None):
         "sign_pack_fused_into_apply": ms_pack == 0.0,
         "standalone": standalone, "graph_replay": graph,
         "momentum_gbs": mom_bytes / (ms_mom * 1e-3) / 1e9 if ms_mom else None,
+        "power_iter": ({"ms_per_step": ms_pi, "algorithmic_gbs": pi_bytes / (ms_pi * 1e-3) / 1e9,
+                        "frac_of_hbm_peak": pi_bytes / (ms_pi * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                        "bytes": "(2P+1) passes over the bf16 X of all workers and, with a local polar step, "
+                                 "over the voted matrices"} if ms_pi else None),
         "per_class": per_class, "workspace_GB": ws / 1e9,
     }
     del w, mom, grad, plan
@@ -371,6 +379,8 @@ def main():
                                                    if main_res["sign_vote_gbs"] else None),
                       "sign_pack_fused_into_apply": main_res["sign_pack_fused_into_apply"]},
         "momentum_gbs": main_res["momentum_gbs"],
+        "momentum_frac_of_hbm_peak": main_res["momentum_gbs"] / HBM_PEAK_GBS if main_res["momentum_gbs"] else None,
+        "power_iter": main_res["power_iter"],
         "per_class_ms": {k: round(v["ms_per_step"], 4) for k, v in main_res["per_class"].items()},
         "workspace_GB": main_res["workspace_GB"],
         "graph_replay": main_res["graph_replay"],
@@ -390,6 +400,8 @@ def main():
             e["sign_pack_gbs"] = a["standalone"]["sign_pack_gbs"]
             e["vote_gbs"] = a["standalone"]["vote_gbs"]
             e["in_step_sign_vote_gbs"] = a["sign_vote_gbs"]
+            if a["power_iter"]:
+                e["power_iter"] = {k: a["power_iter"][k] for k in ("ms_per_step", "algorithmic_gbs", "frac_of_hbm_peak")}
             e["per_class_ms"] = {k: round(v["ms_per_step"], 4) for k, v in a["per_class"].items()}
             line["also"].append(e)
     if not args.no_cpu_baseline:

@@ -207,7 +207,8 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* args);
 #define SM_K_UPDATE 5
 #define SM_K_OTHER 6
 #define SM_K_NS_SMALL 7
-#define SM_K_COUNT 8
+#define SM_K_POWER_ITER 8
+#define SM_K_COUNT 9
 int signmuon_profile_enable(signmuon_ctx* ctx, unsigned class_mask);
 int signmuon_profile_reset(signmuon_ctx* ctx);
 int signmuon_profile_read(signmuon_ctx* ctx, int kernel_class, int64_t* launches, double* total_ms);

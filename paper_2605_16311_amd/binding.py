@@ -22,7 +22,7 @@ SM_SCALE_FRO, SM_SCALE_SPECTRAL, SM_SCALE_NONE = 0, 1, 2
 SM_SIGN_1BIT, SM_SIGN_INT8 = 0, 1
 SM_VOTE_BITS, SM_VOTE_INT8, SM_VOTE_BF16, SM_VOTE_F32 = 0, 1, 2, 3
 (SM_K_MOMENTUM, SM_K_NS_GRAM, SM_K_NS_APPLY, SM_K_SIGN_PACK, SM_K_VOTE,
- SM_K_UPDATE, SM_K_OTHER, SM_K_NS_SMALL, SM_K_COUNT) = range(9)
+ SM_K_UPDATE, SM_K_OTHER, SM_K_NS_SMALL, SM_K_POWER_ITER, SM_K_COUNT) = range(10)
 
 SCALES = {"fro": SM_SCALE_FRO, "spectral": SM_SCALE_SPECTRAL, "none": SM_SCALE_NONE}
 SIGN_FMTS = {"1bit": SM_SIGN_1BIT, "int8": SM_SIGN_INT8}

@@ -121,7 +121,8 @@ int get_plan(signmuon_ctx* ctx, int slot, int n, const int* rows, const int* col
     c.off_sig = take((size_t)batch * 4);
     c.off_inv = take((size_t)batch * 4);
     c.off_partial = take((size_t)batch * c.chunks * 4);
-    total_pi += (long long)c.count * M * (sm_round_up(c.rows, 8) + c.cp * (1 + (c.rows + SM_PI_ROW_CHUNK - 1) / SM_PI_ROW_CHUNK));
+    // per matrix: u, v and one partial X^T u per row chunk (the fused pass has the smaller chunks)
+    total_pi += (long long)c.count * M * (sm_round_up(c.rows, 8) + c.cp * (1 + (c.rows + SM_PI_FUSED_ROWS - 1) / SM_PI_FUSED_ROWS));
   }
   pl->off_pi = take((size_t)total_pi * 4);
   pl->off_signs.resize(n);
@@ -593,7 +594,7 @@ int spectral_sigma(signmuon_ctx* ctx, ns_plan* pl, int buf, int items, int items
     D.part = D.v + (long long)items * cl.cp;
     D.chunks = chunks;
     D.pad_ = 0;
-    scratch += (long long)items * (up + (long long)cl.cp * (1 + chunks));
+    scratch += (long long)items * (up + (long long)cl.cp * (1 + (cl.rows + SM_PI_FUSED_ROWS - 1) / SM_PI_FUSED_ROWS));
     D.sigma = at<float>(ctx, cl.off_sig) + first;
     D.rows = cl.rows;
     D.cols = cl.cols;

@@ -282,4 +282,6 @@ struct sm_pi_desc {
 };
 constexpr int SM_PI_MAX_GROUP = 40;
 constexpr int SM_PI_ROW_CHUNK = 128;
+constexpr int SM_PI_FUSED_ROWS = 64;       // rows per workgroup of the fused pass
+constexpr int SM_PI_FUSED_MAX_LD = 4096;   // widest matrix (padded columns) the fused pass holds in registers
 int sm_launch_power_iter_group(signmuon_ctx* ctx, const sm_pi_desc* descs, int n, int P, float eps);

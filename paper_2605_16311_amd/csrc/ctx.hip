@@ -213,6 +213,7 @@ const char* signmuon_kernel_name(int k) {
     case SM_K_VOTE: return "sm_vote_kernel";
     case SM_K_UPDATE: return "sm_update_kernel";
     case SM_K_OTHER: return "other";
+    case SM_K_POWER_ITER: return "sm_pi_kernels (PowerIter)";
     default: return "?";
   }
 }

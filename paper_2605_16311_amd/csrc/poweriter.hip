@@ -3,10 +3,18 @@
 //   sigma = |X v|.
 // Grouped over a table of weight blocks, M matrices each: every pass over the X of ALL blocks and
 // workers is one launch (two per table when the set has more blocks than a table holds).
+// Matrices of up to SM_PI_FUSED_MAX_LD padded columns take the fused form: one pass over X yields both
+// u = X v and w = X^T u, because row i's share of w, u_i X_i, needs only that row's own product u_i:
+// a wave holds a row in registers, reduces u_i over its lanes and adds u_i X_i into per-lane sums.
+// The two normalisations of a round are scalars, so they are applied afterwards
+// (v' = (w / cu) / (|w / cu| + eps), cu = |u| + eps): P rounds and the final |X v| read X P + 1
+// times instead of 2 P + 1.
 // X is the bf16 working copy [rows][ld] with zero padding up to ld (a multiple of 64); vectors
 // and sums are fp32, u padded to a multiple of 8 and v to ld with zeros.  Every reduction runs
 // in a fixed order (no atomics), so sigma is reproducible.
 #include "common.h"
+
+#include <algorithm>
 
 namespace {
 
@@ -107,9 +115,101 @@ __global__ void __launch_bounds__(TPB) sm_pi_xtu_kernel(const pi_args a) {
   }
 }
 
-// One workgroup per matrix.  which = 0: v <- v0 / (|v0| + eps), zero-padded to ld.
+// Fused pass: u[item][row] = <X_row, v> for the rows of a chunk of SM_PI_FUSED_ROWS rows and, with AXPY,
+// part[item][chunk][j] = sum over those rows of u_row X[row][j].  A workgroup owns one chunk of one matrix;
+// wave w takes rows w, w + 4, ... of it, two at a time (both rows' loads are issued before either is
+// used); a lane owns columns 512 t + 8 lane .. + 7 of strip t < NS and keeps its part of v and of the sums
+// in registers.  The four waves' sums are added in wave order.
+template <int NS, bool AXPY>
+__global__ void __launch_bounds__(TPB) sm_pi_fused_kernel(const pi_args a) {
+  __shared__ float part[AXPY ? 3 : 1][AXPY ? NS * 512 : 1];
+  int local;
+  const sm_pi_desc& D = find_desc(a, blockIdx.x, local);
+  const int chunks = (D.rows + SM_PI_FUSED_ROWS - 1) / SM_PI_FUSED_ROWS;
+  const int item = local / chunks, chunk = local - item * chunks;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int r0 = chunk * SM_PI_FUSED_ROWS, r1 = min(D.rows, r0 + SM_PI_FUSED_ROWS);
+  const bf16_t* xb = D.x + (long long)item * D.stride;
+  const float* v = D.v + (long long)item * D.ld;
+  float* u = D.u + (long long)item * D.up;
+  float vr[NS][8], acc[NS][8];
+#pragma unroll
+  for (int t = 0; t < NS; ++t) {
+    const int j = 512 * t + 8 * lane;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      vr[t][k] = (j < D.ld) ? v[j + k] : 0.f;
+      acc[t][k] = 0.f;
+    }
+  }
+  for (int i = r0 + wv; i < r1; i += 8) {
+    const int i2 = i + 4;
+    u32x4 x0[NS], x1[NS];
+#pragma unroll
+    for (int t = 0; t < NS; ++t) {
+      const int j = 512 * t + 8 * lane;
+      x0[t] = x1[t] = u32x4{0u, 0u, 0u, 0u};
+      if (j < D.ld) {
+        x0[t] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xb + (long long)i * D.ld + j));
+        if (i2 < r1) x1[t] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xb + (long long)i2 * D.ld + j));
+      }
+    }
+    float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+    for (int t = 0; t < NS; ++t)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        s0 += __uint_as_float(x0[t][q] << 16) * vr[t][2 * q] + __uint_as_float(x0[t][q] & 0xFFFF0000u) * vr[t][2 * q + 1];
+        s1 += __uint_as_float(x1[t][q] << 16) * vr[t][2 * q] + __uint_as_float(x1[t][q] & 0xFFFF0000u) * vr[t][2 * q + 1];
+      }
+    // every lane gets the row's product (butterfly: the same value in all lanes)
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      s0 += __shfl_xor(s0, off, 64);
+      s1 += __shfl_xor(s1, off, 64);
+    }
+    if (lane == 0) {
+      u[i] = s0;
+      if (i2 < r1) u[i2] = s1;
+    }
+    if (AXPY) {
+#pragma unroll
+      for (int t = 0; t < NS; ++t)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          acc[t][2 * q] += __uint_as_float(x0[t][q] << 16) * s0;
+          acc[t][2 * q + 1] += __uint_as_float(x0[t][q] & 0xFFFF0000u) * s0;
+          acc[t][2 * q] += __uint_as_float(x1[t][q] << 16) * s1;
+          acc[t][2 * q + 1] += __uint_as_float(x1[t][q] & 0xFFFF0000u) * s1;
+        }
+    }
+  }
+  if (AXPY) {
+    if (wv > 0) {
+#pragma unroll
+      for (int t = 0; t < NS; ++t)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) part[wv - 1][512 * t + 8 * lane + k] = acc[t][k];
+    }
+    __syncthreads();
+    if (wv == 0) {
+      float* o = D.part + ((long long)item * chunks + chunk) * D.ld;
+#pragma unroll
+      for (int t = 0; t < NS; ++t) {
+        const int j = 512 * t + 8 * lane;
+        if (j < D.ld) {
+#pragma unroll
+          for (int k = 0; k < 8; ++k) o[j + k] = ((acc[t][k] + part[0][j + k]) + part[1][j + k]) + part[2][j + k];
+        }
+      }
+    }
+  }
+}
+
+// One workgroup per matrix.  which = 0:// One workgroup per matrix.  which = 0: v <- v0 / (|v0| + eps), zero-padded to ld.
 // which = 1: u <- u / (|u| + eps).  which = 2: v <- s / (|s| + eps) with s the sum of the row chunks'
-// partial X^T u.  which = 3: sigma = |u|.
+// partial X^T u.  which = 3: sigma = |u|.  which = 4 (after a fused pass, u and the partial sums not yet
+// normalised): cu = |u| + eps, s = (sum of the chunks' partial X^T u) / cu, v <- s / (|s| + eps).
 __global__ void __launch_bounds__(TPB) sm_pi_normalize_kernel(const pi_args a, int which) {
   __shared__ float red[4];
   __shared__ float nrm;
@@ -119,7 +219,29 @@ __global__ void __launch_bounds__(TPB) sm_pi_normalize_kernel(const pi_args a, i
   const float* src;
   float* dst;
   int n, n_out;
-  if (which == 0) {
+  if (which == 4) {
+    const float* uu = D.u + (long long)item * D.up;
+    float su = 0.f;
+    for (int i = threadIdx.x; i < D.rows; i += TPB) su += uu[i] * uu[i];
+    su = wave_sum(su);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = su;
+    __syncthreads();
+    if (threadIdx.x == 0) nrm = sqrtf((red[0] + red[1]) + (red[2] + red[3]));
+    __syncthreads();
+    const float inv_cu = 1.0f / (nrm + a.eps);
+    __syncthreads();  // nrm and red are reused below
+    const int chunks = (D.rows + SM_PI_FUSED_ROWS - 1) / SM_PI_FUSED_ROWS;
+    dst = D.v + (long long)item * D.ld;
+    const float* pp = D.part + (long long)item * chunks * D.ld;
+    for (int i = threadIdx.x; i < D.cols; i += TPB) {
+      float t = 0.f;
+      for (int ch = 0; ch < chunks; ++ch) t += pp[(long long)ch * D.ld + i];
+      dst[i] = t * inv_cu;
+    }
+    __syncthreads();
+    src = dst;
+    n = n_out = D.cols;
+  } else if (which == 0) {
     src = D.v0 + (long long)item * D.v0_stride;
     dst = D.v + (long long)item * D.ld;
     n = D.cols;
@@ -156,7 +278,84 @@ __global__ void __launch_bounds__(TPB) sm_pi_normalize_kernel(const pi_args a, i
 
 }  // namespace
 
+// strips of 512 columns the fused kernel is instantiated for
+static int fused_strips(int ld) {
+  const int need = (ld + 511) / 512;
+  for (int ns : {1, 2, 3, 4, 6, 8})
+    if (need <= ns) return ns;
+  return 0;
+}
+
+template <bool AXPY>
+static void launch_fused(int ns, unsigned blocks, hipStream_t st, const pi_args& a) {
+  switch (ns) {
+    case 1: hipLaunchKernelGGL((sm_pi_fused_kernel<1, AXPY>), dim3(blocks), dim3(TPB), 0, st, a); break;
+    case 2: hipLaunchKernelGGL((sm_pi_fused_kernel<2, AXPY>), dim3(blocks), dim3(TPB), 0, st, a); break;
+    case 3: hipLaunchKernelGGL((sm_pi_fused_kernel<3, AXPY>), dim3(blocks), dim3(TPB), 0, st, a); break;
+    case 4: hipLaunchKernelGGL((sm_pi_fused_kernel<4, AXPY>), dim3(blocks), dim3(TPB), 0, st, a); break;
+    case 6: hipLaunchKernelGGL((sm_pi_fused_kernel<6, AXPY>), dim3(blocks), dim3(TPB), 0, st, a); break;
+    default: hipLaunchKernelGGL((sm_pi_fused_kernel<8, AXPY>), dim3(blocks), dim3(TPB), 0, st, a); break;
+  }
+}
+
+// Fused form over a table whose matrices all take the same number of column strips `ns`.
+static int power_iter_fused(signmuon_ctx* ctx, const sm_pi_desc* descs, int n, int P, float eps, int ns) {
+  int done = 0;
+  while (done < n) {
+    const int g = std::min(n - done, SM_PI_MAX_GROUP);
+    pi_args a_pass, a_nrm;
+    long long b_pass = 0, b_nrm = 0;
+    for (pi_args* a : {&a_pass, &a_nrm}) {
+      a->n = g;
+      a->eps = eps;
+    }
+    for (int i = 0; i < g; ++i) {
+      const sm_pi_desc& d = descs[done + i];
+      if (d.ld % 64 || d.up % 8 || d.up < d.rows || !sm_aligned(d.x, 16) || d.stride % 8 || !sm_aligned(d.v, 16))
+        return sm_fail(ctx, SM_EINVAL, "internal: power iteration operands not padded/aligned");
+      a_pass.d[i] = a_nrm.d[i] = d;
+      a_pass.d[i].block_begin = (int)b_pass;
+      a_nrm.d[i].block_begin = (int)b_nrm;
+      b_pass += (long long)((d.rows + SM_PI_FUSED_ROWS - 1) / SM_PI_FUSED_ROWS) * d.items;
+      b_nrm += d.items;
+    }
+    if (b_pass > 0x7FFFFFFFLL) return sm_fail(ctx, SM_EUNSUPPORTED, "power iteration: too many rows for one launch");
+    if (b_nrm > 0) {
+      sm_launch_scope sc(ctx, SM_K_POWER_ITER);
+      auto normalize = [&](int which) {
+        hipLaunchKernelGGL(sm_pi_normalize_kernel, dim3((unsigned)b_nrm), dim3(TPB), 0, ctx->stream, a_nrm, which);
+      };
+      normalize(0);
+      for (int p = 0; p < P; ++p) {
+        launch_fused<true>(ns, (unsigned)b_pass, ctx->stream, a_pass);
+        normalize(4);
+      }
+      launch_fused<false>(ns, (unsigned)b_pass, ctx->stream, a_pass);
+      normalize(3);
+    }
+    SM_HIP(ctx, hipGetLastError());
+    done += g;
+  }
+  return SM_OK;
+}
+
 int sm_launch_power_iter_group(signmuon_ctx* ctx, const sm_pi_desc* descs, int n, int P, float eps) {
+  // the fused form serves the matrices that fit its register budget; wider ones take a pass per product
+  // (one set of launches per strip count in use, so that narrow matrices do not run the wide kernel)
+  std::vector<sm_pi_desc> wide;
+  for (int ns : {1, 2, 3, 4, 6, 8}) {
+    std::vector<sm_pi_desc> bucket;
+    for (int i = 0; i < n; ++i)
+      if (descs[i].ld <= SM_PI_FUSED_MAX_LD && fused_strips(descs[i].ld) == ns) bucket.push_back(descs[i]);
+    if (bucket.empty()) continue;
+    const int rc = power_iter_fused(ctx, bucket.data(), (int)bucket.size(), P, eps, ns);
+    if (rc != SM_OK) return rc;
+  }
+  for (int i = 0; i < n; ++i)
+    if (descs[i].ld > SM_PI_FUSED_MAX_LD) wide.push_back(descs[i]);
+  if (wide.empty()) return SM_OK;
+  descs = wide.data();
+  n = (int)wide.size();
   int done = 0;
   while (done < n) {
     const int g = std::min(n - done, SM_PI_MAX_GROUP);
@@ -182,7 +381,7 @@ int sm_launch_power_iter_group(signmuon_ctx* ctx, const sm_pi_desc* descs, int n
     if (b_xv > 0x7FFFFFFFLL || b_xtu > 0x7FFFFFFFLL)
       return sm_fail(ctx, SM_EUNSUPPORTED, "power iteration: too many rows for one launch");
     if (b_nrm > 0) {
-      sm_launch_scope sc(ctx, SM_K_OTHER);
+      sm_launch_scope sc(ctx, SM_K_POWER_ITER);
       auto normalize = [&](int which) {
         hipLaunchKernelGGL(sm_pi_normalize_kernel, dim3((unsigned)b_nrm), dim3(TPB), 0, ctx->stream, a_nrm, which);
       };

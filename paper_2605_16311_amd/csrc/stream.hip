@@ -299,36 +299,86 @@ __global__ void __launch_bounds__(TPB) sm_sign_pack_bits_kernel(const sp_args a)
 // words are added into PLANES binary counter planes with ripple carries
 // (M < 2^PLANES), then the planes are compared with the threshold ceil(M/2)
 // bit-serially from the top plane down.
+// Adds the set bits of `x` into the bit-sliced counter `plane` (ripple carry).
+template <int PLANES, typename W>
+__device__ __forceinline__ void planes_add(W (&plane)[PLANES], W x) {
+#pragma unroll
+  for (int k = 0; k < PLANES; ++k) {
+    const W t = plane[k] & x;
+    plane[k] ^= x;
+    x = t;
+  }
+}
+
+// Bit mask of the positions whose count is >= T.
+template <int PLANES, typename W>
+__device__ __forceinline__ W planes_ge(const W (&plane)[PLANES], unsigned T) {
+  W gt = 0, eq = ~(W)0;
+#pragma unroll
+  for (int k = PLANES - 1; k >= 0; --k) {
+    const W tb = ((T >> k) & 1u) ? ~(W)0 : (W)0;
+    gt |= eq & plane[k] & ~tb;
+    eq &= ~(plane[k] ^ tb);
+  }
+  return gt | eq;
+}
+
+// Workers are read eight at a time: all eight loads of a group are issued before the first is
+// added, so a thread keeps 8 x 16 bytes in flight (rows beyond M read as zero words, which
+// count nothing).
+constexpr int VOTE_GROUP = 8;
+
 template <int PLANES>
 __global__ void __launch_bounds__(TPB) sm_vote_bits_kernel(const unsigned long long* __restrict__ signs, int M,
                                                            long long words, long long stride_words,
                                                            long long n, unsigned long long* __restrict__ voted) {
-  const long long wi = (long long)blockIdx.x * TPB + threadIdx.x;
-  if (wi >= words) return;
-  unsigned long long plane[PLANES];
+  typedef __attribute__((ext_vector_type(2))) unsigned long long u64x2;
+  // a thread owns the word pair 2 t, 2 t + 1 (rows are 8-byte aligned with any stride: the pair is
+  // read with one 16-byte load only where row base and stride allow it)
+  const long long w0 = ((long long)blockIdx.x * TPB + threadIdx.x) * 2;
+  if (w0 >= words) return;
+  const bool pair = (w0 + 1 < words);
+  const bool vec = pair && ((stride_words & 1) == 0) && ((reinterpret_cast<uintptr_t>(signs) & 15) == 0);
+  unsigned long long p0[PLANES], p1[PLANES];
 #pragma unroll
-  for (int k = 0; k < PLANES; ++k) plane[k] = 0;
-  for (int p = 0; p < M; ++p) {
-    unsigned long long carry = __builtin_nontemporal_load(signs + (long long)p * stride_words + wi);
+  for (int k = 0; k < PLANES; ++k) p0[k] = p1[k] = 0;
+  for (int pb = 0; pb < M; pb += VOTE_GROUP) {
+    unsigned long long a[VOTE_GROUP], b[VOTE_GROUP];
 #pragma unroll
-    for (int k = 0; k < PLANES; ++k) {
-      const unsigned long long t = plane[k] & carry;
-      plane[k] ^= carry;
-      carry = t;
+    for (int q = 0; q < VOTE_GROUP; ++q) {
+      a[q] = b[q] = 0;
+      if (pb + q < M) {
+        const unsigned long long* src = signs + (long long)(pb + q) * stride_words + w0;
+        if (vec) {
+          const u64x2 v = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(src));
+          a[q] = v[0];
+          b[q] = v[1];
+        } else {
+          a[q] = __builtin_nontemporal_load(src);
+          if (pair) b[q] = __builtin_nontemporal_load(src + 1);
+        }
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < VOTE_GROUP; ++q) {
+      planes_add<PLANES>(p0, a[q]);
+      planes_add<PLANES>(p1, b[q]);
     }
   }
   const unsigned T = (unsigned)((M + 1) / 2);  // vote = (count >= T)
-  unsigned long long gt = 0, eq = ~0ull;
+  unsigned long long v[2] = {planes_ge<PLANES>(p0, T), planes_ge<PLANES>(p1, T)};
 #pragma unroll
-  for (int k = PLANES - 1; k >= 0; --k) {
-    const unsigned long long tb = ((T >> k) & 1u) ? ~0ull : 0ull;
-    gt |= eq & plane[k] & ~tb;
-    eq &= ~(plane[k] ^ tb);
+  for (int h = 0; h < 2; ++h) {
+    const long long rem = n - (w0 + h) * 64;
+    if (rem < 64) v[h] &= (rem <= 0) ? 0ull : ((1ull << rem) - 1ull);
   }
-  unsigned long long v = gt | eq;
-  const long long rem = n - wi * 64;
-  if (rem < 64) v &= (rem <= 0) ? 0ull : ((1ull << rem) - 1ull);
-  voted[wi] = v;
+  if (pair && ((reinterpret_cast<uintptr_t>(voted) & 15) == 0)) {
+    const u64x2 o = {v[0], v[1]};
+    __builtin_nontemporal_store(o, reinterpret_cast<u64x2*>(voted + w0));
+  } else {
+    voted[w0] = v[0];
+    if (pair) voted[w0 + 1] = v[1];
+  }
 }
 
 // Voted bits for any M (used beyond 255 workers): one thread = one byte.
@@ -709,7 +759,7 @@ int sm_launch_vote(signmuon_ctx* ctx, const sm_vote_args& v) {
     sm_launch_scope sc(ctx, SM_K_VOTE);
     if (v.fmt == SM_SIGN_1BIT) {
       const long long words = (n + 63) / 64;
-      const dim3 grid((unsigned)((words + TPB - 1) / TPB));
+      const dim3 grid((unsigned)(((words + 1) / 2 + TPB - 1) / TPB));  // two words per thread
       const unsigned long long* sp = reinterpret_cast<const unsigned long long*>(v.signs);
       unsigned long long* vp = reinterpret_cast<unsigned long long*>(v.voted);
       if (v.M < 8)
@@ -756,71 +806,87 @@ int sm_launch_vote(signmuon_ctx* ctx, const sm_vote_args& v) {
 // writes 8 consecutive bf16 per store (4 stores), and steps 4 consecutive weights per load
 // and store (8 of each).  For tables whose entries have n % 32 == 0, no counts output and, if
 // a voted matrix is asked for, the flat bf16 form.
+// A wave takes VW_GROUPS runs of 64 consecutive words; the loads of all runs (eight workers at a time) are
+// issued before the first is counted.
+constexpr int VW_GROUPS = 2;
+
 template <int PLANES>
 __global__ void __launch_bounds__(TPB) sm_vote_wide_kernel(const vote_g_args g) {
   int di = 0;
   while (di + 1 < g.n && (int)blockIdx.x >= g.d[di + 1].block_begin) ++di;
   const vote_x_args& a = g.d[di];
   const long long words = a.n >> 5;
-  const long long w0 = (long long)(blockIdx.x - a.block_begin) * TPB + (threadIdx.x & ~63);  // the wave's first word
   const int lane = threadIdx.x & 63;
-  const long long wi = w0 + lane;
-  unsigned v = 0;
-  if (wi < words) {
-    const unsigned* base = reinterpret_cast<const unsigned*>(a.signs) + wi;
-    const long long stride_w = a.stride_bytes >> 2;
-    unsigned plane[PLANES];
+  // the wave's first word: a workgroup covers TPB * VW_GROUPS words
+  const long long wbase = ((long long)(blockIdx.x - a.block_begin) * TPB + (threadIdx.x & ~63)) * VW_GROUPS;
+  const long long stride_w = a.stride_bytes >> 2;
+  const unsigned* sbase = reinterpret_cast<const unsigned*>(a.signs);
+  unsigned plane[VW_GROUPS][PLANES];
 #pragma unroll
-    for (int k = 0; k < PLANES; ++k) plane[k] = 0;
-    for (int p = 0; p < a.M; ++p) {
-      unsigned carry = __builtin_nontemporal_load(base + (long long)p * stride_w);
+  for (int r = 0; r < VW_GROUPS; ++r)
 #pragma unroll
-      for (int k = 0; k < PLANES; ++k) {
-        const unsigned t = plane[k] & carry;
-        plane[k] ^= carry;
-        carry = t;
+    for (int k = 0; k < PLANES; ++k) plane[r][k] = 0;
+  for (int pb = 0; pb < a.M; pb += VOTE_GROUP) {
+    unsigned x[VW_GROUPS][VOTE_GROUP];
+#pragma unroll
+    for (int r = 0; r < VW_GROUPS; ++r) {
+      const long long wi = wbase + 64 * r + lane;
+#pragma unroll
+      for (int q = 0; q < VOTE_GROUP; ++q) {
+        x[r][q] = 0;
+        if (wi < words && pb + q < a.M) x[r][q] = __builtin_nontemporal_load(sbase + (long long)(pb + q) * stride_w + wi);
       }
     }
-    const unsigned T = (unsigned)((a.M + 1) / 2);
-    unsigned gt = 0, eq = ~0u;
 #pragma unroll
-    for (int k = PLANES - 1; k >= 0; --k) {
-      const unsigned tb = ((T >> k) & 1u) ? ~0u : 0u;
-      gt |= eq & plane[k] & ~tb;
-      eq &= ~(plane[k] ^ tb);
-    }
-    v = gt | eq;
+    for (int r = 0; r < VW_GROUPS; ++r)
+#pragma unroll
+      for (int q = 0; q < VOTE_GROUP; ++q) planes_add<PLANES>(plane[r], x[r][q]);
   }
-  if (a.voted) {
-    bf16_t* o = reinterpret_cast<bf16_t*>(a.voted) + w0 * 32;
+  const unsigned T = (unsigned)((a.M + 1) / 2);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      // chunk 64 k + lane of the wave's 256 chunks of 8 entries: byte (lane & 3) of word 16 k + lane / 4
-      const unsigned word = __shfl(v, 16 * k + (lane >> 2), 64);
-      const unsigned bits = (word >> (8 * (lane & 3))) & 0xFFu;
-      if (w0 + 16 * k + (lane >> 2) < words) {
-        u32x4 h;
+  for (int r = 0; r < VW_GROUPS; ++r) {
+    const long long w0 = wbase + 64 * r;  // the run's first word
+    if (w0 >= words) break;               // wave-uniform
+    const unsigned v = (w0 + lane < words) ? planes_ge<PLANES>(plane[r], T) : 0u;
+    if (a.voted) {
+      bf16_t* o = reinterpret_cast<bf16_t*>(a.voted) + w0 * 32;
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-          h[q] = (((bits >> (2 * q)) & 1u) ? 0x3F80u : 0xBF80u) | ((((bits >> (2 * q + 1)) & 1u) ? 0x3F80u : 0xBF80u) << 16);
-        *reinterpret_cast<u32x4*>(o + (64 * k + lane) * 8) = h;
+      for (int k = 0; k < 4; ++k) {
+        // chunk 64 k + lane of the run's 256 chunks of 8 entries: byte (lane & 3) of word 16 k + lane / 4
+        const unsigned word = __shfl(v, 16 * k + (lane >> 2), 64);
+        const unsigned bits = (word >> (8 * (lane & 3))) & 0xFFu;
+        if (w0 + 16 * k + (lane >> 2) < words) {
+          u32x4 h;
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            h[q] = (((bits >> (2 * q)) & 1u) ? 0x3F80u : 0xBF80u) | ((((bits >> (2 * q + 1)) & 1u) ? 0x3F80u : 0xBF80u) << 16);
+          *reinterpret_cast<u32x4*>(o + (64 * k + lane) * 8) = h;
+        }
       }
     }
-  }
-  if (a.w) {
-    float* wp = a.w + w0 * 32;
+    if (a.w) {
+      float* wp = a.w + w0 * 32;
+      // group 64 k + lane of the run's 512 groups of 4 entries: nibble (lane & 7) of word 8 k + lane / 8;
+      // the eight loads are issued before the first store
+      f32x4 wv[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      // group 64 k + lane of the wave's 512 groups of 4 entries: nibble (lane & 7) of word 8 k + lane / 8
-      const unsigned word = __shfl(v, 8 * k + (lane >> 3), 64);
-      const unsigned bits = (word >> (4 * (lane & 7))) & 0xFu;
-      if (w0 + 8 * k + (lane >> 3) < words) {
-        float4 wv = *reinterpret_cast<float4*>(wp + (64 * k + lane) * 4);
-        wv.x = __fsub_rn(wv.x, __fmul_rn(a.lr, (bits & 1u) ? 1.0f : -1.0f));
-        wv.y = __fsub_rn(wv.y, __fmul_rn(a.lr, (bits & 2u) ? 1.0f : -1.0f));
-        wv.z = __fsub_rn(wv.z, __fmul_rn(a.lr, (bits & 4u) ? 1.0f : -1.0f));
-        wv.w = __fsub_rn(wv.w, __fmul_rn(a.lr, (bits & 8u) ? 1.0f : -1.0f));
-        *reinterpret_cast<float4*>(wp + (64 * k + lane) * 4) = wv;
+      for (int k = 0; k < 8; ++k) {
+        wv[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (w0 + 8 * k + (lane >> 3) < words)
+          wv[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(wp + (64 * k + lane) * 4));
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const unsigned word = __shfl(v, 8 * k + (lane >> 3), 64);
+        const unsigned bits = (word >> (4 * (lane & 7))) & 0xFu;
+        if (w0 + 8 * k + (lane >> 3) < words) {
+          f32x4 o = wv[k];
+          o.x = __fsub_rn(o.x, __fmul_rn(a.lr, (bits & 1u) ? 1.0f : -1.0f));
+          o.y = __fsub_rn(o.y, __fmul_rn(a.lr, (bits & 2u) ? 1.0f : -1.0f));
+          o.z = __fsub_rn(o.z, __fmul_rn(a.lr, (bits & 4u) ? 1.0f : -1.0f));
+          o.w = __fsub_rn(o.w, __fmul_rn(a.lr, (bits & 8u) ? 1.0f : -1.0f));
+          __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(wp + (64 * k + lane) * 4));
+        }
       }
     }
   }
@@ -918,7 +984,7 @@ int sm_launch_vote_group(signmuon_ctx* ctx, const sm_vote_desc* descs, int n, in
     for (int i = 0; i < g; ++i) {
       a.d[i] = descs[done + i];
       a.d[i].block_begin = (int)blocks;
-      const long long threads = wide ? a.d[i].n / 32 : wide8 ? a.d[i].n / 16 : (a.d[i].n + 3) / 4;
+      const long long threads = wide ? (a.d[i].n / 32 + VW_GROUPS - 1) / VW_GROUPS : wide8 ? a.d[i].n / 16 : (a.d[i].n + 3) / 4;
       blocks += (threads + TPB - 1) / TPB;
     }
     if (blocks > 0x7FFFFFFFLL) return sm_fail(ctx, SM_EUNSUPPORTED, "vote: too many entries for one launch");
