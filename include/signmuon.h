@@ -116,6 +116,22 @@ int signmuon_momentum(signmuon_ctx* ctx, float* mom, const float* grad, const fl
                       int M, int rows, int cols, float beta, float weight_decay,
                       void* x_bf16, float* sumsq);
 
+/* The same operation for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Arguments, results and
+ * rounding are those of signmuon_momentum, bit for bit.  The per-chunk partial sums behind
+ * `sumsq` go to a static device array of SM_NOALLOC_SCRATCH_BYTES that the library holds on
+ * every GPU it runs on (instead of context scratch grown on demand); the call allocates and
+ * frees nothing, takes no timing taps, and only queues kernels on the context's stream.
+ * Limit: M * ceil(rows * cols / 1024) * 4 <= SM_NOALLOC_SCRATCH_BYTES, beyond it SM_EUNSUPPORTED
+ * and nothing is queued.  All contexts of one GPU share the array: calls whose kernels may
+ * overlap on one GPU (different streams, no ordering between them) race on it; calls on one
+ * stream are ordered and safe.  Nothing in it needs clearing: every partial sum a call reads
+ * was written by that call. */
+#define SM_NOALLOC_SCRATCH_BYTES (4u << 20)
+int signmuon_momentum_noalloc(signmuon_ctx* ctx, float* mom, const float* grad, const float* w,
+                              int M, int rows, int cols, float beta, float weight_decay,
+                              void* x_bf16, float* sumsq);
+
 /* ---- a2-a4: PolarNS (Alg. PolarNS; Alg. PowerIter; idealized NS algorithm) */
 /* In place on x[batch][rows][cols] (dtype SM_F32 or SM_BF16):
  *   Y0 = X / max(sigma, eps);  `steps` times  Y <- Y (a I + b A + c A^2), A = Y^T Y,

@@ -31,11 +31,12 @@ VOTE_FMTS = {"bits": SM_VOTE_BITS, "int8": SM_VOTE_INT8, "bf16": SM_VOTE_BF16, "
 SM_OPT_GEMM_TILE, SM_OPT_NS_PATH, SM_OPT_NS_STORE = 0, 1, 2
 NS_PATHS = {"pairs": 0, "single": 1, "stepwise": 2}
 NS_STORES = {"upper": 0, "full": 1}
+SM_NOALLOC_SCRATCH_BYTES = 4 << 20
 
 EXPORTS = [
     "signmuon_create", "signmuon_destroy", "signmuon_set_option", "signmuon_get_option",
     "signmuon_strerror", "signmuon_last_error",
-    "signmuon_workspace_bytes", "signmuon_momentum", "signmuon_polar_ns",
+    "signmuon_workspace_bytes", "signmuon_momentum", "signmuon_momentum_noalloc", "signmuon_polar_ns",
     "signmuon_sign_pack",
     "signmuon_majority_vote", "signmuon_step", "signmuon_profile_enable", "signmuon_profile_reset",
     "signmuon_profile_read", "signmuon_profile_work", "signmuon_kernel_name",
@@ -74,6 +75,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.signmuon_workspace_bytes.argtypes = [vp]
     lib.signmuon_workspace_bytes.restype = C.c_size_t
     lib.signmuon_momentum.argtypes = [vp, vp, vp, vp, i32, i32, i32, f32, f32, vp, vp]
+    lib.signmuon_momentum_noalloc.argtypes = [vp, vp, vp, vp, i32, i32, i32, f32, f32, vp, vp]
     lib.signmuon_polar_ns.argtypes = [vp, vp, i32, i32, i32, i32, C.POINTER(f32), i32, i32, i32, f32, vp]
     lib.signmuon_sign_pack.argtypes = [vp, vp, i32, i32, i64, i32, vp, i64]
     lib.signmuon_majority_vote.argtypes = [vp, vp, i32, i32, i64, i64, vp, i32, vp, vp, f32]
@@ -188,6 +190,14 @@ def signmuon_momentum(ctx, mom, grad, w, beta, weight_decay=0.0, x_bf16=None, su
     assert mom.shape == grad.shape and mom.dtype == grad.dtype == torch.float32
     ctx._check(_lib.signmuon_momentum(ctx._h, _ptr(mom), _ptr(grad), _ptr(w), M, r, c, beta, weight_decay,
                                       _ptr(x_bf16), _ptr(sumsq)), "signmuon_momentum")
+
+
+def signmuon_momentum_noalloc(ctx, mom, grad, w, beta, weight_decay=0.0, x_bf16=None, sumsq=None):
+    """signmuon_momentum without any device allocation (static scratch inside the library)."""
+    M, r, c = grad.shape
+    assert mom.shape == grad.shape and mom.dtype == grad.dtype == torch.float32
+    ctx._check(_lib.signmuon_momentum_noalloc(ctx._h, _ptr(mom), _ptr(grad), _ptr(w), M, r, c, beta, weight_decay,
+                                              _ptr(x_bf16), _ptr(sumsq)), "signmuon_momentum_noalloc")
 
 
 def signmuon_polar_ns(ctx, x, steps, coeffs=(1.5, -0.5, 0.0), scale="fro", power_iters=2, eps=1e-12, v0=None):

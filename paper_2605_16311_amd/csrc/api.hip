@@ -707,6 +707,26 @@ int signmuon_momentum(signmuon_ctx* ctx, float* mom, const float* grad, const fl
                       reinterpret_cast<float*>(ctx->aux));
 }
 
+int signmuon_momentum_noalloc(signmuon_ctx* ctx, float* mom, const float* grad, const float* w, int M, int rows,
+                              int cols, float beta, float weight_decay, void* x_bf16, float* sumsq) {
+  if (!ctx) return SM_EINVAL;
+  int rc = momentum_check(ctx, mom, grad, w, M, rows, cols, beta, weight_decay, x_bf16, sumsq);
+  if (rc != SM_OK) return rc;
+  const long long chunks = ((long long)rows * cols + SM_MOM_CHUNK - 1) / SM_MOM_CHUNK;
+  if ((unsigned long long)M * chunks * 4ull > SM_STATIC_SCRATCH_BYTES)
+    return sm_fail(ctx, SM_EUNSUPPORTED,
+                   "momentum_noalloc: M * ceil(rows*cols/1024) partial sums exceed the static scratch (" +
+                       std::to_string(SM_STATIC_SCRATCH_BYTES) + " bytes)");
+  if (!ctx->static_scratch) return sm_fail(ctx, SM_EHIP, "momentum_noalloc: no static scratch on this device");
+  // timing taps create HIP events on demand: not on this path
+  const unsigned taps = ctx->profiling;
+  ctx->profiling = 0;
+  rc = momentum_one(ctx, mom, grad, w, M, rows, cols, beta, weight_decay, x_bf16, sumsq,
+                    reinterpret_cast<float*>(ctx->static_scratch));
+  ctx->profiling = taps;
+  return rc;
+}
+
 int signmuon_polar_ns(signmuon_ctx* ctx, void* x, int dtype, int batch, int rows, int cols, const float* coeffs,
                       int steps, int scale, int power_iters, float eps, const float* v0) {
   if (!ctx) return SM_EINVAL;

@@ -41,6 +41,10 @@ struct signmuon_ctx {
   void* aux = nullptr;
   size_t aux_bytes = 0;
 
+  // device address of the library's static scratch array on this context's device
+  // (signmuon_momentum_noalloc); fixed size SM_STATIC_SCRATCH_BYTES
+  void* static_scratch = nullptr;
+
   // tuning switches (signmuon_set_option)
   int opt[SM_OPT_COUNT] = {};
   int n_cu = 256;  // compute units of the device
@@ -73,6 +77,7 @@ struct sm_launch_scope {
   ~sm_launch_scope();
 };
 
+constexpr size_t SM_STATIC_SCRATCH_BYTES = SM_NOALLOC_SCRATCH_BYTES;
 constexpr int SM_WS_STEP = 0, SM_WS_NS = 1;
 // Ensures the arena of workspace `slot` holds at least `bytes` and makes it the current arena;
 // contents (and the slot's plan) are lost when it grows.

@@ -4,6 +4,7 @@
 #include <stdio.h>
 
 #include <algorithm>
+#include <mutex>
 
 int sm_fail(signmuon_ctx* ctx, int code, const std::string& msg) {
   if (ctx) ctx->last_error = msg;
@@ -38,6 +39,32 @@ sm_launch_scope::~sm_launch_scope() {
 }
 
 void sm_plan_free(signmuon_ctx* ctx, int slot);  // api.hip
+
+// Scratch of the entry point that allocates nothing (signmuon_momentum_noalloc): per-chunk partial
+// sums of squares.  Every GPU the library runs on holds its own copy of this array until the
+// process ends.  Host code never uses the array's name as an address: signmuon_create asks the
+// runtime for the device address once per device and kernels receive that pointer as an argument.
+static __device__ __align__(256) unsigned char scratch[SM_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+// Device address of `scratch` on device `dev`, which must be the current device.
+hipError_t static_scratch_address(int dev, void** out) {
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+}  // namespace
 
 int sm_arena_reserve(signmuon_ctx* ctx, int slot, size_t bytes) {
   signmuon_ctx::workspace& w = ctx->ws[slot];
@@ -98,6 +125,11 @@ int signmuon_create(signmuon_ctx** out, void* hip_stream, size_t workspace_bytes
   c->stream = (hipStream_t)hip_stream;
   c->device = dev;
   c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  e = static_scratch_address(dev, &c->static_scratch);
+  if (e != hipSuccess) {
+    delete c;
+    return SM_EHIP;
+  }
   if (workspace_bytes_hint) {
     const int rc = sm_arena_reserve(c, SM_WS_STEP, workspace_bytes_hint);
     if (rc != SM_OK) {
