@@ -91,7 +91,11 @@ int signmuon_destroy(signmuon_ctx* ctx);
 #define SM_OPT_NS_STORE 2  /* storage of the symmetric s x s matrices of the recurrence: */
 #define SM_NS_STORE_UPPER 0   /*   blocks on and above the diagonal only (default) */
 #define SM_NS_STORE_FULL 1    /*   whole matrices */
-#define SM_OPT_COUNT 3
+#define SM_OPT_POWER_ITER 3 /* passes of Alg. PowerIter over X: */
+#define SM_PI_AUTO 0          /*   fused where that is faster by a launch-cost estimate (default) */
+#define SM_PI_FUSED 1         /*   u = X v and X^T u from one read of X wherever the matrix is narrow enough */
+#define SM_PI_SEPARATE 2      /*   one pass per product */
+#define SM_OPT_COUNT 4
 int signmuon_set_option(signmuon_ctx* ctx, int option, int value);
 int signmuon_get_option(const signmuon_ctx* ctx, int option, int* value);
 /* Static text for a status code. */
@@ -100,6 +104,7 @@ const char* signmuon_strerror(int status);
 const char* signmuon_last_error(const signmuon_ctx* ctx);
 /* Bytes of device workspace the context currently holds. */
 size_t signmuon_workspace_bytes(const signmuon_ctx* ctx);
+
 
 /* ---- a1: weight decay + momentum (Alg. 1 steps 5-6; Alg. 2 steps 6-7) --- */
 /* For every worker p < M:  g = grad[p] + weight_decay * w ;

@@ -28,7 +28,8 @@ SCALES = {"fro": SM_SCALE_FRO, "spectral": SM_SCALE_SPECTRAL, "none": SM_SCALE_N
 SIGN_FMTS = {"1bit": SM_SIGN_1BIT, "int8": SM_SIGN_INT8}
 VOTE_FMTS = {"bits": SM_VOTE_BITS, "int8": SM_VOTE_INT8, "bf16": SM_VOTE_BF16, "f32": SM_VOTE_F32}
 
-SM_OPT_GEMM_TILE, SM_OPT_NS_PATH, SM_OPT_NS_STORE = 0, 1, 2
+SM_OPT_GEMM_TILE, SM_OPT_NS_PATH, SM_OPT_NS_STORE, SM_OPT_POWER_ITER = 0, 1, 2, 3
+POWER_ITERS = {"auto": 0, "fused": 1, "separate": 2}
 NS_PATHS = {"pairs": 0, "single": 1, "stepwise": 2}
 NS_STORES = {"upper": 0, "full": 1}
 SM_NOALLOC_SCRATCH_BYTES = 4 << 20
@@ -119,7 +120,7 @@ class Context:
     """signmuon_ctx bound to torch's current stream on the current device."""
 
     def __init__(self, stream: "torch.cuda.Stream | None" = None, workspace_bytes_hint: int = 0, *,
-                 gemm_tile: int = 0, ns_path: str = "pairs", ns_store: str = "upper"):
+                 gemm_tile: int = 0, ns_path: str = "pairs", ns_store: str = "upper", power_iter: str = "auto"):
         if not torch.cuda.is_available():
             raise SignMuonError("no HIP device: libsignmuon has no CPU path")
         self.stream = stream if stream is not None else torch.cuda.current_stream()
@@ -131,6 +132,7 @@ class Context:
         self.set_option(SM_OPT_GEMM_TILE, gemm_tile)
         self.set_option(SM_OPT_NS_PATH, NS_PATHS[ns_path])
         self.set_option(SM_OPT_NS_STORE, NS_STORES[ns_store])
+        self.set_option(SM_OPT_POWER_ITER, POWER_ITERS[power_iter])
 
     def set_option(self, option: int, value: int):
         self._check(_lib.signmuon_set_option(self._h, int(option), int(value)), "signmuon_set_option")

@@ -164,6 +164,7 @@ int signmuon_set_option(signmuon_ctx* ctx, int option, int value) {
     case SM_OPT_GEMM_TILE: ok = (value == 0 || value == 128 || value == 256); break;
     case SM_OPT_NS_PATH: ok = (value >= SM_NS_PATH_PAIRS && value <= SM_NS_PATH_STEPWISE); break;
     case SM_OPT_NS_STORE: ok = (value == SM_NS_STORE_UPPER || value == SM_NS_STORE_FULL); break;
+    case SM_OPT_POWER_ITER: ok = (value >= SM_PI_AUTO && value <= SM_PI_SEPARATE); break;
     default: break;
   }
   if (!ok) return sm_fail(ctx, SM_EINVAL, "set_option: unknown option or value");

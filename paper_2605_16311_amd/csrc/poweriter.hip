@@ -278,10 +278,11 @@ __global__ void __launch_bounds__(TPB) sm_pi_normalize_kernel(const pi_args a, i
 
 }  // namespace
 
-// strips of 512 columns the fused kernel is instantiated for
+// strips of 512 columns the fused kernel is instantiated for (narrow matrices share the 3-strip kernel: a
+// strip beyond the matrix issues no loads)
 static int fused_strips(int ld) {
   const int need = (ld + 511) / 512;
-  for (int ns : {1, 2, 3, 4, 6, 8})
+  for (int ns : {3, 4, 6, 8})
     if (need <= ns) return ns;
   return 0;
 }
@@ -289,8 +290,6 @@ static int fused_strips(int ld) {
 template <bool AXPY>
 static void launch_fused(int ns, unsigned blocks, hipStream_t st, const pi_args& a) {
   switch (ns) {
-    case 1: hipLaunchKernelGGL((sm_pi_fused_kernel<1, AXPY>), dim3(blocks), dim3(TPB), 0, st, a); break;
-    case 2: hipLaunchKernelGGL((sm_pi_fused_kernel<2, AXPY>), dim3(blocks), dim3(TPB), 0, st, a); break;
     case 3: hipLaunchKernelGGL((sm_pi_fused_kernel<3, AXPY>), dim3(blocks), dim3(TPB), 0, st, a); break;
     case 4: hipLaunchKernelGGL((sm_pi_fused_kernel<4, AXPY>), dim3(blocks), dim3(TPB), 0, st, a); break;
     case 6: hipLaunchKernelGGL((sm_pi_fused_kernel<6, AXPY>), dim3(blocks), dim3(TPB), 0, st, a); break;
@@ -341,18 +340,39 @@ static int power_iter_fused(signmuon_ctx* ctx, const sm_pi_desc* descs, int n, i
 
 int sm_launch_power_iter_group(signmuon_ctx* ctx, const sm_pi_desc* descs, int n, int P, float eps) {
   // the fused form serves the matrices that fit its register budget; wider ones take a pass per product
-  // (one set of launches per strip count in use, so that narrow matrices do not run the wide kernel)
+  // One set of launches per strip count in use, so that narrow matrices do not run the wide kernel.  The
+  // fused form saves two of five passes over X and costs more launches (7 per strip count in use instead
+  // of 10 in all): it is taken when the bytes saved outweigh them at about 10 us a launch.
   std::vector<sm_pi_desc> wide;
-  for (int ns : {1, 2, 3, 4, 6, 8}) {
-    std::vector<sm_pi_desc> bucket;
+  double bytes = 0.0;
+  int buckets = 0;
+  bool any_wide = false;
+  for (int ns : {3, 4, 6, 8}) {
+    bool used = false;
     for (int i = 0; i < n; ++i)
-      if (descs[i].ld <= SM_PI_FUSED_MAX_LD && fused_strips(descs[i].ld) == ns) bucket.push_back(descs[i]);
-    if (bucket.empty()) continue;
-    const int rc = power_iter_fused(ctx, bucket.data(), (int)bucket.size(), P, eps, ns);
-    if (rc != SM_OK) return rc;
+      if (descs[i].ld <= SM_PI_FUSED_MAX_LD && fused_strips(descs[i].ld) == ns) {
+        used = true;
+        bytes += 2.0 * descs[i].rows * descs[i].ld * descs[i].items;
+      }
+    buckets += used;
+  }
+  for (int i = 0; i < n; ++i) any_wide = any_wide || descs[i].ld > SM_PI_FUSED_MAX_LD;
+  const double saved_us = 2.0 * bytes / 5e6;  // two passes at about 5 TB/s
+  const double extra_us = 10.0 * (7.0 * buckets + (any_wide ? 10.0 : 0.0) - 10.0);
+  const int mode = ctx->opt[SM_OPT_POWER_ITER];
+  const bool fuse = P > 0 && buckets > 0 && mode != SM_PI_SEPARATE && (mode == SM_PI_FUSED || saved_us > extra_us);
+  if (fuse) {
+    for (int ns : {3, 4, 6, 8}) {
+      std::vector<sm_pi_desc> bucket;
+      for (int i = 0; i < n; ++i)
+        if (descs[i].ld <= SM_PI_FUSED_MAX_LD && fused_strips(descs[i].ld) == ns) bucket.push_back(descs[i]);
+      if (bucket.empty()) continue;
+      const int rc = power_iter_fused(ctx, bucket.data(), (int)bucket.size(), P, eps, ns);
+      if (rc != SM_OK) return rc;
+    }
   }
   for (int i = 0; i < n; ++i)
-    if (descs[i].ld > SM_PI_FUSED_MAX_LD) wide.push_back(descs[i]);
+    if (!fuse || descs[i].ld > SM_PI_FUSED_MAX_LD) wide.push_back(descs[i]);
   if (wide.empty()) return SM_OK;
   descs = wide.data();
   n = (int)wide.size();

@@ -295,10 +295,9 @@ __global__ void __launch_bounds__(TPB) sm_sign_pack_bits_kernel(const sp_args a)
 }
 
 // ------------------------------------------------------------------ vote
-// Voted bits only: one thread = one 64-bit word.  Bit-sliced counting: the M
-// words are added into PLANES binary counter planes with ripple carries
-// (M < 2^PLANES), then the planes are compared with the threshold ceil(M/2)
-// bit-serially from the top plane down.
+// Voted bits only.  Bit-sliced counting: the M words of a position are added into
+// PLANES binary counter planes with ripple carries (M < 2^PLANES), then the planes
+// are compared with the threshold ceil(M/2) bit-serially from the top plane down.
 // Adds the set bits of `x` into the bit-sliced counter `plane` (ripple carry).
 template <int PLANES, typename W>
 __device__ __forceinline__ void planes_add(W (&plane)[PLANES], W x) {
@@ -328,56 +327,73 @@ __device__ __forceinline__ W planes_ge(const W (&plane)[PLANES], unsigned T) {
 // count nothing).
 constexpr int VOTE_GROUP = 8;
 
+// A thread owns VB_PAIRS pairs of 64-bit words, TPB pairs apart (rows are 8-byte aligned with any stride: a
+// pair is read with one 16-byte load only where row base and stride allow it).
+constexpr int VB_PAIRS = 2;
+
 template <int PLANES>
 __global__ void __launch_bounds__(TPB) sm_vote_bits_kernel(const unsigned long long* __restrict__ signs, int M,
                                                            long long words, long long stride_words,
                                                            long long n, unsigned long long* __restrict__ voted) {
   typedef __attribute__((ext_vector_type(2))) unsigned long long u64x2;
-  // a thread owns the word pair 2 t, 2 t + 1 (rows are 8-byte aligned with any stride: the pair is
-  // read with one 16-byte load only where row base and stride allow it)
-  const long long w0 = ((long long)blockIdx.x * TPB + threadIdx.x) * 2;
-  if (w0 >= words) return;
-  const bool pair = (w0 + 1 < words);
-  const bool vec = pair && ((stride_words & 1) == 0) && ((reinterpret_cast<uintptr_t>(signs) & 15) == 0);
-  unsigned long long p0[PLANES], p1[PLANES];
+  const bool vec_ok = ((stride_words & 1) == 0) && ((reinterpret_cast<uintptr_t>(signs) & 15) == 0);
+  long long w0[VB_PAIRS];
+  unsigned long long p0[VB_PAIRS][PLANES], p1[VB_PAIRS][PLANES];
 #pragma unroll
-  for (int k = 0; k < PLANES; ++k) p0[k] = p1[k] = 0;
+  for (int r = 0; r < VB_PAIRS; ++r) {
+    w0[r] = (((long long)blockIdx.x * VB_PAIRS + r) * TPB + threadIdx.x) * 2;
+#pragma unroll
+    for (int k = 0; k < PLANES; ++k) p0[r][k] = p1[r][k] = 0;
+  }
+  if (w0[0] >= words) return;
   for (int pb = 0; pb < M; pb += VOTE_GROUP) {
-    unsigned long long a[VOTE_GROUP], b[VOTE_GROUP];
+    unsigned long long a[VB_PAIRS][VOTE_GROUP], b[VB_PAIRS][VOTE_GROUP];
 #pragma unroll
-    for (int q = 0; q < VOTE_GROUP; ++q) {
-      a[q] = b[q] = 0;
-      if (pb + q < M) {
-        const unsigned long long* src = signs + (long long)(pb + q) * stride_words + w0;
-        if (vec) {
-          const u64x2 v = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(src));
-          a[q] = v[0];
-          b[q] = v[1];
-        } else {
-          a[q] = __builtin_nontemporal_load(src);
-          if (pair) b[q] = __builtin_nontemporal_load(src + 1);
+    for (int r = 0; r < VB_PAIRS; ++r) {
+      const bool live = w0[r] < words, pair = w0[r] + 1 < words;
+#pragma unroll
+      for (int q = 0; q < VOTE_GROUP; ++q) {
+        a[r][q] = b[r][q] = 0;
+        if (live && pb + q < M) {
+          const unsigned long long* src = signs + (long long)(pb + q) * stride_words + w0[r];
+          if (vec_ok && pair) {
+            const u64x2 v = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(src));
+            a[r][q] = v[0];
+            b[r][q] = v[1];
+          } else {
+            a[r][q] = __builtin_nontemporal_load(src);
+            if (pair) b[r][q] = __builtin_nontemporal_load(src + 1);
+          }
         }
       }
     }
 #pragma unroll
-    for (int q = 0; q < VOTE_GROUP; ++q) {
-      planes_add<PLANES>(p0, a[q]);
-      planes_add<PLANES>(p1, b[q]);
-    }
+    for (int r = 0; r < VB_PAIRS; ++r)
+#pragma unroll
+      for (int q = 0; q < VOTE_GROUP; ++q) {
+        planes_add<PLANES>(p0[r], a[r][q]);
+        planes_add<PLANES>(p1[r], b[r][q]);
+      }
   }
   const unsigned T = (unsigned)((M + 1) / 2);  // vote = (count >= T)
-  unsigned long long v[2] = {planes_ge<PLANES>(p0, T), planes_ge<PLANES>(p1, T)};
+  const bool out_vec = (reinterpret_cast<uintptr_t>(voted) & 15) == 0;
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const long long rem = n - (w0 + h) * 64;
-    if (rem < 64) v[h] &= (rem <= 0) ? 0ull : ((1ull << rem) - 1ull);
-  }
-  if (pair && ((reinterpret_cast<uintptr_t>(voted) & 15) == 0)) {
-    const u64x2 o = {v[0], v[1]};
-    __builtin_nontemporal_store(o, reinterpret_cast<u64x2*>(voted + w0));
-  } else {
-    voted[w0] = v[0];
-    if (pair) voted[w0 + 1] = v[1];
+  for (int r = 0; r < VB_PAIRS; ++r) {
+    if (w0[r] >= words) break;
+    const bool pair = w0[r] + 1 < words;
+    unsigned long long v[2] = {planes_ge<PLANES>(p0[r], T), planes_ge<PLANES>(p1[r], T)};
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const long long rem = n - (w0[r] + h) * 64;
+      if (rem < 64) v[h] &= (rem <= 0) ? 0ull : ((1ull << rem) - 1ull);
+    }
+    if (pair && out_vec) {
+      const u64x2 o = {v[0], v[1]};
+      __builtin_nontemporal_store(o, reinterpret_cast<u64x2*>(voted + w0[r]));
+    } else {
+      voted[w0[r]] = v[0];
+      if (pair) voted[w0[r] + 1] = v[1];
+    }
   }
 }
 
@@ -759,7 +775,7 @@ int sm_launch_vote(signmuon_ctx* ctx, const sm_vote_args& v) {
     sm_launch_scope sc(ctx, SM_K_VOTE);
     if (v.fmt == SM_SIGN_1BIT) {
       const long long words = (n + 63) / 64;
-      const dim3 grid((unsigned)(((words + 1) / 2 + TPB - 1) / TPB));  // two words per thread
+      const dim3 grid((unsigned)(((words + 1) / 2 + TPB * VB_PAIRS - 1) / (TPB * VB_PAIRS)));  // VB_PAIRS word pairs per thread
       const unsigned long long* sp = reinterpret_cast<const unsigned long long*>(v.signs);
       unsigned long long* vp = reinterpret_cast<unsigned long long*>(v.voted);
       if (v.M < 8)
@@ -799,9 +815,9 @@ int sm_launch_vote(signmuon_ctx* ctx, const sm_vote_args& v) {
   return SM_OK;
 }
 
-// Expanding vote over 1-bit signs, wide form: one thread = one 32-bit word of every worker's
-// buffer, counted bit-sliced (PLANES binary counter planes, M < 2^PLANES) and compared with
-// ceil(M/2) as in sm_vote_bits_kernel.  The 2048 votes of a wave are then spread over its
+// Expanding vote over 1-bit signs, wide form: a lane takes one 32-bit word of every worker's
+// buffer per run, counted bit-sliced (PLANES binary counter planes, M < 2^PLANES) and compared with
+// ceil(M/2) as in sm_vote_bits_kernel.  The 2048 votes of a run are then spread over the wave's
 // lanes so that every store (and every load of W) covers consecutive addresses: lane l
 // writes 8 consecutive bf16 per store (4 stores), and steps 4 consecutive weights per load
 // and store (8 of each).  For tables whose entries have n % 32 == 0, no counts output and, if

@@ -548,6 +548,17 @@ def test_step_spectral(P, vctx):
     run_step_case(P, vctx, [(128, 256), (256, 128)], 2, sign_fmt="1bit", Kp=2, scale="spectral")
 
 
+@pytest.mark.parametrize("mode", ["fused", "separate", "auto"])
+def test_step_spectral_power_iteration_forms(P, mode):
+    """Alg. PowerIter over a set that spans every form: matrices for each column-strip count of the fused pass
+    (one read of X for X v and X^T u), one too wide for it (a pass per product), ragged row chunks and padding."""
+    shapes = [(72, 4608), (200, 160), (96, 1800), (130, 2304), (64, 3000), (70, 4000), (300, 64)]
+    ctx = P.Context(power_iter=mode)
+    run_step_case(P, ctx, shapes, 2, sign_fmt="1bit", Kp=1, K=3, scale="spectral", stream=37)
+    torch.cuda.synchronize()
+    ctx.close()
+
+
 def test_nan_worker_on_a_padded_shape_does_not_leak_into_other_blocks(P):
     """A NaN in one worker's gradient turns that worker's whole matrix NaN (every sign -1), zero padding of its
     slots in the working layout included.  After the vote those slots hold other blocks' voted matrices, so
