@@ -301,6 +301,56 @@ def cpu_baseline(name, budget_s=15.0):
                       f"by nominal Newton-Schulz work"}
 
 
+def mfma_loop_ceiling():
+    """Runs the register-resident MFMA loop (paper_2605_16311_amd/mfma_peak, a program of its own, before this
+    process touches the GPU): what the matrix cores sustain with nothing else going on, for constant operands
+    and for operands of full range, whose switching power lowers the clock the part holds."""
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2605_16311_amd", "mfma_peak")
+    if not os.path.exists(exe):
+        return None
+    try:
+        out = subprocess.run([exe, "60"], capture_output=True, text=True, timeout=120).stdout
+    except Exception:
+        return None
+    res, mode = {}, None
+    for ln in out.splitlines():
+        if ln.startswith("operands:"):
+            mode = ln.split(":", 1)[1].strip()
+        elif "GEMM's shape" in ln and "bf16" in ln and mode:
+            try:
+                res[mode] = float(ln.split("ms")[1].split("TFLOP/s")[0])
+            except (IndexError, ValueError):
+                pass
+    return {"tflops_bf16_by_operands": res, "what": "v_mfma_f32_32x32x16_bf16 loop, registers only, 8 waves/CU, 4x2 "
+            "accumulators per wave as in the GEMM kernel"} if res else None
+
+
+def library_gemm_yardstick(torch):
+    """torch.matmul in bf16 (the vendor's GEMM library) on the shapes of the dominant products, in the same run and
+    on the same device: a yardstick for what a tuned GEMM reaches on this part, not part of the path."""
+    out = {}
+    for name, (b, m, n, k) in {"384 x (768 x 768 x 768)": (384, 768, 768, 768),
+                               "16 x (4096 x 4096 x 4096)": (16, 4096, 4096, 4096),
+                               "8192 x 8192 x 8192": (1, 8192, 8192, 8192)}.items():
+        A = torch.randn((b, m, k), device="cuda").to(torch.bfloat16)
+        Bm = torch.randn((b, k, n), device="cuda").to(torch.bfloat16)
+        for _ in range(3):
+            torch.bmm(A, Bm)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+        for s, e in ev:
+            s.record()
+            torch.bmm(A, Bm)
+            e.record()
+        torch.cuda.synchronize()
+        ms = sorted(s.elapsed_time(e) for s, e in ev)[len(ev) // 2]
+        out[name] = {"median_ms": ms, "tflops": 2.0 * b * m * n * k / ms / 1e9,
+                     "frac_of_mfma_peak": 2.0 * b * m * n * k / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS}
+        del A, Bm
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -311,6 +361,8 @@ def main():
                     help="further workloads (comma separated) reported in the same line under 'also' ('' to skip); "
                          "the two large sets run 3 timed steps, the small ones 5 x --steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-calibration", action="store_true",
+                    help="skip the register-resident MFMA loop and the library GEMM yardstick (context figures)")
     ap.add_argument("--scale", default=None, choices=["fro", "spectral"],
                     help="scale of Alg. PolarNS: Frobenius norm or PowerIter with P = 2 (default: the workload's own)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -321,6 +373,7 @@ def main():
         print("bench.py: this build runs on ONE GPU (the M workers are a batch dimension); "
               "--gpus N with N > 1 is not supported", file=sys.stderr)
         sys.exit(2)
+    mfma_loop = None if args.no_calibration else mfma_loop_ceiling()     # before this process uses the GPU
     import torch
     import paper_2605_16311_amd as P
     from paper_2605_16311_amd import binding as B
@@ -416,6 +469,9 @@ def main():
                 e["power_iter"] = {k: a["power_iter"][k] for k in ("ms_per_step", "algorithmic_gbs", "frac_of_hbm_peak")}
             e["per_class_ms"] = {k: round(v["ms_per_step"], 4) for k, v in a["per_class"].items()}
             line["also"].append(e)
+    if not args.no_calibration:
+        # context for the fractions of the nominal peak above: neither figure is a target or part of the path
+        line["calibration"] = {"mfma_loop": mfma_loop, "library_gemm_bf16": library_gemm_yardstick(torch)}
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(line))

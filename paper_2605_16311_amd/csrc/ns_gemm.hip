@@ -828,9 +828,20 @@ int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, bool sym, int klass) {
   }
   int ts = ctx->opt[SM_OPT_GEMM_TILE];
   if (ts != 128 && ts != 256) {
-    // 256 x 256 tiles once there are enough of them to keep 256 CUs busy for several rounds
+    // 256 x 256 tiles once there are enough of them to keep 256 CUs busy for several rounds, unless the
+    // matrices fill them badly (a 384-wide matrix covers one and a half: the small tile then computes a
+    // third less)
+    auto tile_area = [&](int t) {
+      double area = 0.0;
+      for (int i = 0; i < args.n_prob; ++i) {
+        const sm_gemm_prob& P = args.p[i];
+        const double tm = (P.M + t - 1) / t, tn = (P.N + t - 1) / t;
+        area += (gram ? tm * (tm + 1) / 2 : tm * tn) * (double)t * t * P.batch;
+      }
+      return area;
+    };
     fill_tiles(args, gram, 256);
-    ts = (args.total_tiles >= 1024) ? 256 : 128;
+    ts = (args.total_tiles >= 1024 && tile_area(256) <= 1.15 * tile_area(128)) ? 256 : 128;
   }
   const int most = fill_tiles(args, gram, ts);
   if (args.total_tiles == 0) return SM_OK;

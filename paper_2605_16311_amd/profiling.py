@@ -42,8 +42,8 @@ CLASSES = {
 
 
 def bench_cmd(workload, steps, warmup, extra=()):
-    return ["python3", BENCH, "--no-cpu-baseline", "--workload", workload, "--steps", str(steps), "--warmup", str(warmup),
-            "--also", "", *extra]
+    return ["python3", BENCH, "--no-cpu-baseline", "--no-calibration", "--workload", workload, "--steps", str(steps),
+            "--warmup", str(warmup), "--also", "", *extra]
 
 
 def pass_commands(workload):
@@ -102,8 +102,9 @@ def summarise_kt(out, workload, prof):
     rows = list(csv.DictReader(open(f)))
     lines = [f"rocprofv3 kernel trace, workload {workload}, one MI355X",
              "command (from /tmp, TMPDIR=/tmp):", "  " + printable(pass_commands(workload)["kt"]),
-             "(3 warm-up + 10 timed + 10 per-class steps, the standalone sign-pack / vote calls, then the captured and",
-             " replayed steps of bench.py's graph_replay; bench_kernel_stats.csv, top rows)", "",
+             "(3 warm-up + 10 timed steps, the same 10 with event taps on the GEMM launches, 10 with taps on every class,",
+             " the standalone sign-pack / vote calls, then the captured and replayed steps of bench.py's graph_replay;",
+             " bench_kernel_stats.csv, top rows)", "",
              "%-72s %6s %11s %10s %7s" % ("kernel", "calls", "total_ms", "avg_us", "pct")]
     avg = {}
     for r in rows:

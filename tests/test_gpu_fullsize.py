@@ -71,12 +71,13 @@ def full_step_check(P, name, ns_blocks, **ctx_opts):
         assert np.array_equal(mom[i].cpu().numpy().view(np.uint32), m_ref.view(np.uint32)), f"momentum block {i}"
         U = u_out[i].float().cpu().numpy()
         assert np.isfinite(U).all()
-        # properties that hold at any size: after cubic steps from a Frobenius-scaled start the
-        # spectrum lies in (0, 1], so ||U||_F^2 <= min(r, c); a power-iteration scale underestimates the
-        # largest singular value, which the cubic map then takes to at most 1 within a few percent
+        # a property that holds at any size: the cubic map 1.5 x - 0.5 x^3 takes every singular value in
+        # (0, sqrt(3)) into (0, 1], so after at least one step ||U||_F^2 <= min(r, c) both from a Frobenius-scaled
+        # start (x <= 1) and from a power-iteration scale, which underestimates the largest singular value by
+        # far less than sqrt(3); 2 % covers the bf16 rounding (measured: at most 1.001)
         fro2 = np.sum(U.astype(np.float64) ** 2, axis=(1, 2))
         rank_ratio = max(rank_ratio, float(fro2.max()) / min(r, c))
-        assert np.all(fro2 <= min(r, c) * (1.02 if scale == "fro" else 1.1)), f"block {i}: ||U||_F^2 {fro2.max()} > rank bound"
+        assert np.all(fro2 <= min(r, c) * 1.02), f"block {i}: ||U||_F^2 {fro2.max()} > rank bound"
         if i in ns_blocks:
             for p in (0, M - 1):
                 ref = O.polar_ns(m_ref[p], K, scale=scale, power_iters=2, v0=V0[i][p], dtype=np.float32)
