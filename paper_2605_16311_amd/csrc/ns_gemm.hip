@@ -699,6 +699,12 @@ __global__ void __launch_bounds__(NTH) sm_ns_gemm_kernel(const sm_gemm_args args
         ++tn;
       }
       tm = t;
+    } else if (P.tiles_n < P.tiles_m) {
+      // The side with fewer tiles runs fastest: the tiles that share a panel of the long operand
+      // (Y in the apply) are neighbours in the list, so they run at the same time on one XCD and
+      // the panel crosses HBM once.
+      tm = t / P.tiles_n;
+      tn = t - tm * P.tiles_n;
     } else {
       tn = t / P.tiles_m;
       tm = t - tn * P.tiles_m;
