@@ -206,38 +206,60 @@ __global__ void __launch_bounds__(TPB) sm_pi_fused_kernel(const pi_args a) {
   }
 }
 
-// One workgroup per matrix.  which = 0:// One workgroup per matrix.  which = 0: v <- v0 / (|v0| + eps), zero-padded to ld.
+// Sum over the row chunks' partial sums of one column, in chunk order, the loads of eight chunks issued
+// before the first is added.
+__device__ __forceinline__ float chunk_sum(const float* __restrict__ pp, int chunks, long long ld) {
+  float t = 0.f;
+  int ch = 0;
+  for (; ch + 8 <= chunks; ch += 8) {
+    float x[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) x[k] = pp[(ch + k) * ld];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t += x[k];
+  }
+  for (; ch < chunks; ++ch) t += pp[ch * ld];
+  return t;
+}
+
+// One workgroup of TPN threads per matrix.  which = 0: v <- v0 / (|v0| + eps), zero-padded to ld.
 // which = 1: u <- u / (|u| + eps).  which = 2: v <- s / (|s| + eps) with s the sum of the row chunks'
 // partial X^T u.  which = 3: sigma = |u|.  which = 4 (after a fused pass, u and the partial sums not yet
 // normalised): cu = |u| + eps, s = (sum of the chunks' partial X^T u) / cu, v <- s / (|s| + eps).
-__global__ void __launch_bounds__(TPB) sm_pi_normalize_kernel(const pi_args a, int which) {
-  __shared__ float red[4];
+constexpr int TPN = 1024;
+__global__ void __launch_bounds__(TPN) sm_pi_normalize_kernel(const pi_args a, int which) {
+  __shared__ float red[TPN / 64];
   __shared__ float nrm;
   int local;
   const sm_pi_desc& D = find_desc(a, blockIdx.x, local);
   const int item = local;
+  // sqrt of the workgroup's sum, the waves' sums added in wave order
+  auto block_norm = [&](float ss) {
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float t = 0.f;
+      for (int w = 0; w < TPN / 64; ++w) t += red[w];
+      nrm = sqrtf(t);
+    }
+    __syncthreads();
+    const float r = nrm;
+    __syncthreads();  // red and nrm may be written again
+    return r;
+  };
   const float* src;
   float* dst;
   int n, n_out;
   if (which == 4) {
     const float* uu = D.u + (long long)item * D.up;
     float su = 0.f;
-    for (int i = threadIdx.x; i < D.rows; i += TPB) su += uu[i] * uu[i];
-    su = wave_sum(su);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = su;
-    __syncthreads();
-    if (threadIdx.x == 0) nrm = sqrtf((red[0] + red[1]) + (red[2] + red[3]));
-    __syncthreads();
-    const float inv_cu = 1.0f / (nrm + a.eps);
-    __syncthreads();  // nrm and red are reused below
+    for (int i = threadIdx.x; i < D.rows; i += TPN) su += uu[i] * uu[i];
+    const float inv_cu = 1.0f / (block_norm(su) + a.eps);
     const int chunks = (D.rows + SM_PI_FUSED_ROWS - 1) / SM_PI_FUSED_ROWS;
     dst = D.v + (long long)item * D.ld;
     const float* pp = D.part + (long long)item * chunks * D.ld;
-    for (int i = threadIdx.x; i < D.cols; i += TPB) {
-      float t = 0.f;
-      for (int ch = 0; ch < chunks; ++ch) t += pp[(long long)ch * D.ld + i];
-      dst[i] = t * inv_cu;
-    }
+    for (int i = threadIdx.x; i < D.cols; i += TPN) dst[i] = chunk_sum(pp + i, chunks, D.ld) * inv_cu;
     __syncthreads();
     src = dst;
     n = n_out = D.cols;
@@ -249,11 +271,7 @@ __global__ void __launch_bounds__(TPB) sm_pi_normalize_kernel(const pi_args a, i
   } else if (which == 2) {
     dst = D.v + (long long)item * D.ld;
     const float* pp = D.part + (long long)item * D.chunks * D.ld;
-    for (int i = threadIdx.x; i < D.cols; i += TPB) {
-      float t = 0.f;
-      for (int ch = 0; ch < D.chunks; ++ch) t += pp[(long long)ch * D.ld + i];
-      dst[i] = t;
-    }
+    for (int i = threadIdx.x; i < D.cols; i += TPN) dst[i] = chunk_sum(pp + i, D.chunks, D.ld);
     __syncthreads();
     src = dst;
     n = n_out = D.cols;
@@ -262,18 +280,14 @@ __global__ void __launch_bounds__(TPB) sm_pi_normalize_kernel(const pi_args a, i
     n = n_out = D.rows;
   }
   float ss = 0.f;
-  for (int i = threadIdx.x; i < n; i += TPB) ss += src[i] * src[i];
-  ss = wave_sum(ss);
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    nrm = sqrtf((red[0] + red[1]) + (red[2] + red[3]));
-    if (which == 3) D.sigma[item] = nrm;
+  for (int i = threadIdx.x; i < n; i += TPN) ss += src[i] * src[i];
+  const float nr = block_norm(ss);
+  if (which == 3) {
+    if (threadIdx.x == 0) D.sigma[item] = nr;
+    return;
   }
-  __syncthreads();
-  if (which == 3) return;
-  const float inv = 1.0f / (nrm + a.eps);
-  for (int i = threadIdx.x; i < n_out; i += TPB) dst[i] = (i < n) ? src[i] * inv : 0.f;
+  const float inv = 1.0f / (nr + a.eps);
+  for (int i = threadIdx.x; i < n_out; i += TPN) dst[i] = (i < n) ? src[i] * inv : 0.f;
 }
 
 }  // namespace
@@ -322,7 +336,7 @@ static int power_iter_fused(signmuon_ctx* ctx, const sm_pi_desc* descs, int n, i
     if (b_nrm > 0) {
       sm_launch_scope sc(ctx, SM_K_POWER_ITER);
       auto normalize = [&](int which) {
-        hipLaunchKernelGGL(sm_pi_normalize_kernel, dim3((unsigned)b_nrm), dim3(TPB), 0, ctx->stream, a_nrm, which);
+        hipLaunchKernelGGL(sm_pi_normalize_kernel, dim3((unsigned)b_nrm), dim3(TPN), 0, ctx->stream, a_nrm, which);
       };
       normalize(0);
       for (int p = 0; p < P; ++p) {
@@ -403,7 +417,7 @@ int sm_launch_power_iter_group(signmuon_ctx* ctx, const sm_pi_desc* descs, int n
     if (b_nrm > 0) {
       sm_launch_scope sc(ctx, SM_K_POWER_ITER);
       auto normalize = [&](int which) {
-        hipLaunchKernelGGL(sm_pi_normalize_kernel, dim3((unsigned)b_nrm), dim3(TPB), 0, ctx->stream, a_nrm, which);
+        hipLaunchKernelGGL(sm_pi_normalize_kernel, dim3((unsigned)b_nrm), dim3(TPN), 0, ctx->stream, a_nrm, which);
       };
       auto xv = [&]() { hipLaunchKernelGGL(sm_pi_xv_kernel, dim3((unsigned)b_xv), dim3(TPB), 0, ctx->stream, a_xv); };
       auto xtu = [&]() { hipLaunchKernelGGL(sm_pi_xtu_kernel, dim3((unsigned)b_xtu), dim3(TPB), 0, ctx->stream, a_xtu); };
