@@ -656,6 +656,50 @@ __device__ __forceinline__ void gemm_tile(const sm_gemm_args& args, const sm_gem
   }
 }
 
+// Tile t of a matrix's list.  The list goes through the tile grid in bands of BR tile rows and, inside a band,
+// column by column with the rows running fastest (a symmetric output: only tiles with tile_m <= tile_n; a band
+// starts with the upper triangle of its diagonal block, column by column).  The workgroups of an XCD work on
+// about 32 (TS = 256) or 64 (TS = 128) neighbouring entries of the list at any one time: a run of that length
+// covers BR rows and 8 columns, i.e. it needs BR + 8 operand panels instead of the 16 + 2 of a run down whole
+// columns of a 16 x 16 grid, and every panel it needs is shared by tiles that run together, so it crosses HBM
+// once per run.  A grid of up to BR rows (s <= 1024 at TS = 256) is a single band.
+template <bool SYM, int BR>
+__host__ __device__ __forceinline__ void tile_of(int t, int tiles_m, int tiles_n, int& tm, int& tn) {
+  if (SYM) {
+    const int T = tiles_m;
+    int r0 = 0, h;
+    for (;;) {
+      h = (T - r0 < BR) ? T - r0 : BR;
+      const int cnt = h * (h + 1) / 2 + (T - r0 - h) * h;
+      if (t < cnt || r0 + h >= T) break;
+      t -= cnt;
+      r0 += h;
+    }
+    const int d = h * (h + 1) / 2;
+    if (t < d) {  // diagonal block: (0,0) (0,1) (1,1) (0,2) ...
+      int c = 0;
+      while (t > c) {
+        t -= c + 1;
+        ++c;
+      }
+      tm = r0 + t;
+      tn = r0 + c;
+    } else {
+      t -= d;
+      const int c = t / h;
+      tm = r0 + (t - c * h);
+      tn = r0 + h + c;
+    }
+  } else {
+    const int per_band = BR * tiles_n;
+    const int b = t / per_band;
+    t -= b * per_band;
+    const int h = (tiles_m - b * BR < BR) ? tiles_m - b * BR : BR;
+    tn = t / h;
+    tm = b * BR + (t - tn * h);
+  }
+}
+
 // KIND 0: symmetric output, bf16 operands both KC or both MN; the upper triangle of tiles is computed.
 // KIND 1: general output, bf16 operands (A is KC; B is KC or MN).
 // KIND 2: symmetric output, half-precision operands, both KC.
@@ -692,23 +736,7 @@ __global__ void __launch_bounds__(NTH) sm_ns_gemm_kernel(const sm_gemm_args args
     }
     const sm_gemm_prob& P = args.p[pi];
     int tm, tn;
-    if (SYM) {  // upper triangle, column by column: (0,0) (0,1) (1,1) (0,2) ...
-      tn = 0;
-      while (t > tn) {
-        t -= tn + 1;
-        ++tn;
-      }
-      tm = t;
-    } else if (P.tiles_n < P.tiles_m) {
-      // The side with fewer tiles runs fastest: the tiles that share a panel of the long operand
-      // (Y in the apply) are neighbours in the list, so they run at the same time on one XCD and
-      // the panel crosses HBM once.
-      tm = t / P.tiles_n;
-      tn = t - tm * P.tiles_n;
-    } else {
-      tn = t / P.tiles_m;
-      tm = t - tn * P.tiles_m;
-    }
+    tile_of<SYM, (TS == 256 ? 4 : 8)>(t, P.tiles_m, P.tiles_n, tm, tn);
     if (KIND == 0) {
       if (P.layout == 0)
         gemm_tile<TS, false, false, true, false>(args, P, b, tm, tn, sA0, sA1, sB0, sB1);
@@ -793,6 +821,22 @@ extern "C" int signmuon_debug_tile_ranges(int n_prob, const int* M, const int* N
   for (int x = 0; x < 9; ++x) xcd_begin[x] = a.xcd_begin[x];
   for (int i = 0; i < n_prob; ++i) tile_begin[i] = a.p[i].tile_begin;
   return a.total_tiles;
+}
+
+// Host-side check hook: entry t of the tile list of one matrix with a tiles_m x tiles_n grid of ts-wide tiles
+// (sym: the upper triangle of a square grid), as the kernels decode it.  Returns 0, or -1 on bad arguments.
+extern "C" int signmuon_debug_tile_of(int t, int tiles_m, int tiles_n, int sym, int ts, int* tile_m, int* tile_n) {
+  if (!tile_m || !tile_n || tiles_m < 1 || tiles_n < 1 || (ts != 128 && ts != 256) || (sym && tiles_m != tiles_n)) return -1;
+  const int total = sym ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
+  if (t < 0 || t >= total) return -1;
+  if (sym) {
+    if (ts == 256) tile_of<true, 4>(t, tiles_m, tiles_n, *tile_m, *tile_n);
+    else tile_of<true, 8>(t, tiles_m, tiles_n, *tile_m, *tile_n);
+  } else {
+    if (ts == 256) tile_of<false, 4>(t, tiles_m, tiles_n, *tile_m, *tile_n);
+    else tile_of<false, 8>(t, tiles_m, tiles_n, *tile_m, *tile_n);
+  }
+  return 0;
 }
 
 // Per problem, P.layout bit 0: A is MN-contiguous, bit 1: B is MN-contiguous.  sym: symmetric

@@ -124,6 +124,50 @@ def test_gemm_tile_ranges_cover_the_list_and_balance_cost():
     assert lib.signmuon_debug_tile_ranges(0, None, None, None, None, None, 1, 256, None, None) == -1
 
 
+def test_gemm_tile_order_lists_every_tile_once_and_keeps_neighbours_on_few_panels():
+    """Host logic of the GEMM kernels' tile decode: the list of one matrix names every tile of the grid (of its
+    upper triangle for a symmetric output) exactly once, small grids keep the plain column-by-column order, and
+    on a large grid a run of 32 list neighbours touches few operand panels (row panels of A plus column panels
+    of B), which is what lets the tiles an XCD runs together share their panels in its L2."""
+    import ctypes as C
+    import torch  # noqa: F401
+    lib = C.CDLL(LIB)
+    f = lib.signmuon_debug_tile_of
+    f.restype = C.c_int
+    f.argtypes = [C.c_int] * 5 + [C.POINTER(C.c_int)] * 2
+
+    def order(tm_n, tn_n, sym, ts):
+        total = tm_n * (tm_n + 1) // 2 if sym else tm_n * tn_n
+        out = []
+        for t in range(total):
+            a, b = C.c_int(-1), C.c_int(-1)
+            assert f(t, tm_n, tn_n, int(sym), ts, C.byref(a), C.byref(b)) == 0
+            out.append((a.value, b.value))
+        return out
+
+    for ts in (128, 256):
+        for T in list(range(1, 20)) + [43, 64]:
+            tiles = order(T, T, True, ts)
+            assert sorted(tiles) == sorted((m, n) for n in range(T) for m in range(n + 1)), (ts, T)
+        for tm_n, tn_n in [(1, 1), (3, 12), (12, 3), (16, 43), (43, 16), (5, 7), (9, 1), (1, 9), (17, 17), (8, 32)]:
+            tiles = order(tm_n, tn_n, False, ts)
+            assert sorted(tiles) == sorted((m, n) for m in range(tm_n) for n in range(tn_n)), (ts, tm_n, tn_n)
+    # a grid of one band is listed column by column, rows fastest
+    assert order(3, 3, True, 256) == [(0, 0), (0, 1), (1, 1), (0, 2), (1, 2), (2, 2)]
+    assert order(3, 4, False, 256) == [(m, n) for n in range(4) for m in range(3)]
+    # locality on a large grid of a general product: a run of 32 neighbours of the list (what an XCD works on at
+    # one time) touches about 4 row panels of A and 8 or 9 column panels of B, not 16 + 2
+    for tiles in (order(16, 43, False, 256), order(43, 16, False, 256)):
+        counts = sorted(len({m for m, _ in tiles[i:i + 32]}) + len({n for _, n in tiles[i:i + 32]})
+                        for i in range(0, len(tiles) - 31))
+        assert counts[len(counts) // 2] <= 13 and counts[-1] <= 18, (counts[len(counts) // 2], counts[-1])
+    # bad arguments
+    a, b = C.c_int(), C.c_int()
+    assert f(6, 3, 3, 1, 256, C.byref(a), C.byref(b)) == -1
+    assert f(0, 3, 4, 1, 256, C.byref(a), C.byref(b)) == -1
+    assert f(0, 3, 3, 0, 64, C.byref(a), C.byref(b)) == -1
+
+
 def test_two_step_recurrence_coefficients_reproduce_two_newton_schulz_steps():
     """Host logic of the regrouped Newton-Schulz iteration (Alg. PolarNS with c = 0): on an eigenvalue x of
     the Gram matrix, two steps multiply Y by Q_1 Q_0 with Q_0 = a + b x and Q_1 = a + b x Q_0^2.  The
