@@ -102,7 +102,7 @@ struct sm_mom_desc {
   int chunks;          // chunks per worker
   int block_begin;     // first workgroup of this block in the grouped launch
 };
-constexpr int SM_MOM_MAX_GROUP = 40;
+constexpr int SM_MOM_MAX_GROUP = 52;  // blocks per launch: the table rides in the kernel arguments (4 KB at most)
 constexpr int SM_MOM_CHUNK = 1024;  // elements per workgroup: one 16-byte piece per thread (short-lived workgroups
                                     // keep the four streams of the momentum update close together in memory)
 

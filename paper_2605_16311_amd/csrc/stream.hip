@@ -41,6 +41,7 @@ struct mom_args {
   int start[64];
   sm_mom_desc d[SM_MOM_MAX_GROUP];
 };
+static_assert(sizeof(mom_args) <= 4096, "kernel arguments are limited to 4 KB");
 
 __device__ __forceinline__ float mom_one(float m, float g, float w, const mom_args& a, bool has_wd) {
   if (has_wd) g = __fadd_rn(g, __fmul_rn(a.wd, w));
