@@ -48,6 +48,7 @@ struct signmuon_ctx {
   // tuning switches (signmuon_set_option)
   int opt[SM_OPT_COUNT] = {};
   int n_cu = 256;  // compute units of the device
+  int gemm_flip = 0;  // parity of the GEMM launches so far: every other launch walks its tile ranges backwards
 
   // timing taps
   unsigned profiling = 0;  // bit k set: launches of kernel class k are bracketed with events
@@ -259,6 +260,7 @@ struct sm_gemm_args {
   int in_f16, out_f16, r_f16;
   int sym_store;     // bit 0: the operands hold valid data only in their 256 x 256 blocks on and above the diagonal
                      // (symmetric matrices; half precision, M == N == K); bit 1: write the output that way
+  int reverse;       // an XCD walks its range of the tile list from the end (set by the launcher: every other launch)
   sm_gemm_prob p[SM_GEMM_MAX_PROB];
 };
 // One grouped launch over the problem table.  sym: every problem's output is symmetric (M == N;

@@ -717,9 +717,12 @@ __global__ void __launch_bounds__(NTH) sm_ns_gemm_kernel(const sm_gemm_args args
   // tiles at any one time, so tiles that share operand panels share an L2.
   const int wg = blockIdx.x;
   const int per_xcd_wgs = gridDim.x >> 3;
-  const int xcd_end = args.xcd_begin[(wg & 7) + 1];
+  const int xcd_first = args.xcd_begin[wg & 7], xcd_end = args.xcd_begin[(wg & 7) + 1];
   bool first_tile = true;
-  for (int L = args.xcd_begin[wg & 7] + (wg >> 3); L < xcd_end; L += per_xcd_wgs) {
+  for (int Lf = xcd_first + (wg >> 3); Lf < xcd_end; Lf += per_xcd_wgs) {
+    // every other launch goes through the range backwards: it starts with the matrices the launch before it
+    // wrote last, which are the ones still in the caches
+    const int L = args.reverse ? xcd_first + xcd_end - 1 - Lf : Lf;
     if (!first_tile) __syncthreads();  // the previous tile has been read out of the stage arrays
     first_tile = false;
     int pi = 0;
@@ -895,6 +898,8 @@ int sm_launch_gemm(signmuon_ctx* ctx, sm_gemm_args& args, bool sym, int klass) {
   }
   const int most = fill_tiles(args, gram, ts);
   if (args.total_tiles == 0) return SM_OK;
+  args.reverse = ctx->gemm_flip;
+  ctx->gemm_flip ^= 1;
   // persistent grid: one workgroup per CU (two for the small tile), a multiple of 8, never more than tiles
   int wgs = ctx->n_cu * (ts == 128 ? 2 : 1);
   wgs = std::max(1, std::min(wgs / 8, most)) * 8;
