@@ -344,6 +344,26 @@ def test_polar_ns_against_fp32_oracle(P, vctx, batch, r, c, steps, scale, coeffs
         ns_check(got[b], ref, f"{(batch, r, c, steps, scale, dt)} item {b}")
 
 
+@pytest.mark.parametrize("opts", [dict(gemm_tile=128), dict(gemm_tile=256), dict(gemm_tile=256, ns_store="full"),
+                                  dict(gemm_tile=128, ns_path="stepwise")])
+@pytest.mark.parametrize("r,c", [(1152, 1408), (1408, 1152)])
+def test_polar_ns_on_grids_of_several_tile_bands(P, opts, r, c):
+    """The GEMM kernels list a matrix's tiles in bands of 4 (256-wide tiles) or 8 (128-wide) tile rows.  A short
+    side of 1152 is 4.5 and 9 tiles: the symmetric products and the apply run over a full band and a ragged
+    one, in both operand orientations."""
+    ctx = P.Context(**opts)
+    x = wl.normal((2, r, c), stream=27, block=r, worker=c)
+    xd = dev(wl.to_bf16_bits(x).view(np.int16)).view(torch.bfloat16)
+    xin = wl.from_bf16_bits(wl.to_bf16_bits(x))
+    P.signmuon_polar_ns(ctx, xd, 5, scale="fro")
+    got = xd.float().cpu().numpy()
+    for b in range(2):
+        ns_check(got[b], O.polar_ns(xin[b], 5, O.PAPER_COEFFS, "fro", 2, 1e-12, None, dtype=np.float32),
+                 f"{(r, c, opts)} item {b}")
+    torch.cuda.synchronize()
+    ctx.close()
+
+
 def test_polar_ns_zero_matrix_and_errors(P, ctx):
     x = torch.zeros((2, 64, 128), dtype=torch.float32, device="cuda")
     P.signmuon_polar_ns(ctx, x, 5)
