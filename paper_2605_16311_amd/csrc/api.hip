@@ -884,6 +884,9 @@ int signmuon_step(signmuon_ctx* ctx, const signmuon_step_args* s) {
   }
   rc = sm_launch_momentum(ctx, descs.data(), n, M, s->beta, s->weight_decay);
   if (rc != SM_OK) return rc;
+  // the first GEMM launch (the Gram of Y) walks its tile ranges backwards: it starts with the blocks whose
+  // bf16 copies the momentum kernel wrote last
+  ctx->gemm_flip = 1;
   // the momentum kernel writes the logical entries of X only: restore the zero padding, which an
   // earlier call with a non-finite matrix may have turned into NaN
   rc = clear_padding(ctx, pl, 0, [&](ns_class& cl) { return cl.count * M; });
