@@ -373,6 +373,8 @@ def main():
         print("bench.py: this build runs on ONE GPU (the M workers are a batch dimension); "
               "--gpus N with N > 1 is not supported", file=sys.stderr)
         sys.exit(2)
+    import __graft_entry__
+    __graft_entry__.ensure_built()                                       # loads what is built; compiles only if nothing is
     mfma_loop = None if args.no_calibration else mfma_loop_ceiling()     # before this process uses the GPU
     import torch
     import paper_2605_16311_amd as P

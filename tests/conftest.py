@@ -12,6 +12,12 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def pytest_sessionstart(session):
+    # the tests load the built library; it is compiled here only when there is none
+    import __graft_entry__
+    __graft_entry__.ensure_built()
+
+
 def _gpu_available():
     try:
         import torch
