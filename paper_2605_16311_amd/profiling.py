@@ -10,9 +10,10 @@ the GPU.  Passes:
     fetch  --pmc FETCH_SIZE                           HBM bytes read per dispatch   (with a known-size copy)
     write  --pmc WRITE_SIZE                           HBM bytes written per dispatch
     mfma   --pmc SQ_VALU_MFMA_BUSY_CYCLES ...         matrix-core busy cycles, counted MFMA ops, clock
+    cache  --pmc TCC_HIT_sum TCC_MISS_sum ...         L2 hits and misses, LDS bank conflicts (not in the default set)
     peak   mfma_peak                                  register-resident MFMA loop (no profiler)
 summarise reads DIR and writes <profiles>/<workload>_kernel_trace.txt, _hbm_traffic.txt, _mfma_counters.txt,
-mfma_loop_peak.txt and traffic.json (HBM bytes per launch by kernel class, read by bench.py).
+_cache_counters.txt, mfma_loop_peak.txt and traffic.json (HBM bytes per launch by kernel class, read by bench.py).
 """
 from __future__ import annotations
 
@@ -31,6 +32,8 @@ ROOT = os.path.dirname(HERE)
 BENCH = os.path.join(ROOT, "bench.py")
 MFMA_COUNTERS = ["SQ_VALU_MFMA_BUSY_CYCLES", "SQ_BUSY_CU_CYCLES", "SQ_INSTS_VALU_MFMA_MOPS_BF16",
                  "SQ_INSTS_VALU_MFMA_MOPS_F16", "SQ_WAVE_CYCLES", "SQ_BUSY_CYCLES", "GRBM_GUI_ACTIVE"]
+CACHE_COUNTERS = ["TCC_HIT_sum", "TCC_MISS_sum", "TCC_REQ_sum", "SQ_LDS_BANK_CONFLICT", "SQ_LDS_IDX_ACTIVE",
+                  "TCP_PENDING_STALL_CYCLES_sum"]
 SIMD_PER_XCD, XCDS = 128, 8          # 32 CUs x 4 SIMDs per XCD
 
 # kernel classes of bench.py -> substring of the kernel name
@@ -56,6 +59,8 @@ def pass_commands(workload):
                   *bench_cmd(workload, 3, 1, ["--copy-calibration"])],
         "mfma": ["rocprofv3", "--pmc", *MFMA_COUNTERS, "-d", "{dir}", "-o", "bench", "--output-format", "csv", "--",
                  *bench_cmd(workload, 3, 1)],
+        "cache": ["rocprofv3", "--pmc", *CACHE_COUNTERS, "-d", "{dir}", "-o", "bench", "--output-format", "csv", "--",
+                  *bench_cmd(workload, 3, 1)],
         "peak": [os.path.join(HERE, "mfma_peak"), "200"],
     }
 
@@ -212,6 +217,32 @@ def summarise_mfma(out, workload, prof, kt_avg):
     open(os.path.join(prof, f"{workload}_mfma_counters.txt"), "w").write("\n".join(lines) + "\n")
 
 
+def summarise_cache(out, workload, prof):
+    f = find(out, "cache", "*counter_collection.csv")
+    if not f:
+        return
+    m = counter_means(f)
+    lines = [f"L2 and LDS counters per dispatch from rocprofv3 --pmc, workload {workload}, one MI355X",
+             "command (from /tmp, TMPDIR=/tmp):", "  " + printable(pass_commands(workload)["cache"]),
+             "columns: mean per dispatch.  l2_hit = TCC_HIT_sum / (TCC_HIT_sum + TCC_MISS_sum) over the 128-byte requests of all",
+             "channels of the eight L2s; lds_conflict = SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE (cycles lost to bank conflicts",
+             "per cycle the LDS spent on indexed accesses); tcp_pending = TCP_PENDING_STALL_CYCLES_sum (cycles a CU's vector L1",
+             "could not take a request because of the requests it already had in flight).", "",
+             "%-40s %5s %12s %12s %7s %12s %12s %9s %12s" % ("kernel", "disp", "l2_hit_req", "l2_miss_req", "l2_hit", "lds_conflict",
+                                                          "lds_active", "conflict", "tcp_pending")]
+    for k, d in sorted(m.items(), key=lambda kv: -kv[1].get("TCC_REQ_sum", (0, 0))[1]):
+        if "sm_" not in k:
+            continue
+        n, hit = d.get("TCC_HIT_sum", (0, 0.0))
+        miss = d.get("TCC_MISS_sum", (0, 0.0))[1]
+        bc = d.get("SQ_LDS_BANK_CONFLICT", (0, 0.0))[1]
+        act = d.get("SQ_LDS_IDX_ACTIVE", (0, 0.0))[1]
+        pend = d.get("TCP_PENDING_STALL_CYCLES_sum", (0, 0.0))[1]
+        lines.append("%-40s %5d %12.4g %12.4g %7.3f %12.4g %12.4g %9.3f %12.4g" % (
+            short(k)[:40], n, hit, miss, hit / (hit + miss) if hit + miss else 0.0, bc, act, bc / act if act else 0.0, pend))
+    open(os.path.join(prof, f"{workload}_cache_counters.txt"), "w").write("\n".join(lines) + "\n")
+
+
 def summarise_peak(out, prof):
     f = os.path.join(out, "peak", "run.log")
     if not os.path.exists(f):
@@ -236,6 +267,7 @@ def main():
     kt_avg = summarise_kt(a.out, a.workload, a.profiles)
     summarise_traffic(a.out, a.workload, a.profiles)
     summarise_mfma(a.out, a.workload, a.profiles, kt_avg)
+    summarise_cache(a.out, a.workload, a.profiles)
     summarise_peak(a.out, a.profiles)
 
 
